@@ -1,0 +1,242 @@
+"""Pins for the CPU oracle: each check ties oracle/mdbf_oracle.py to something the
+paper or plain mathematics fixes, not to the oracle itself.  CPU only."""
+import numpy as np
+import pytest
+
+from oracle import mdbf_oracle as orc
+from paper_2512_24545_amd import synth
+
+
+def _tiny(seed, m, n, k, l, T=2, signed=True):
+    L = synth.make_layer(m, n, k, l, seed=seed, env_dtype="f32", env_kind="unit", signed_env=signed)
+    X = synth.make_activations(n, T, seed=seed + 1, x_dtype="f32")
+    return L, X
+
+
+def _args(L):
+    return (L["SA"], L["SB"], L["A"], L["Q"], L["G"], L["B"])
+
+
+# ---- hand-worked example (tests/golden/tiny_mdbf_worked.txt; Eq. "me-dbf-basis") ----
+def test_hand_worked_example(golden_tiny):
+    g = golden_tiny
+    args = (g["SA"].astype(np.int8), g["SB"].astype(np.int8), g["A"], g["Q"], g["G"], g["B"])
+    np.testing.assert_array_equal(orc.dense_reconstruct(*args), g["W"])
+    np.testing.assert_array_equal(orc.forward_dense(*args, g["X"]), g["Y"])
+    Y, Z = orc.forward_factored(*args, g["X"], return_intermediates=True)
+    np.testing.assert_array_equal(Y, g["Y"])
+    np.testing.assert_array_equal(Z, g["Z"])
+    np.testing.assert_array_equal(orc.forward_sum_of_dbf(*args, g["X"]), g["Y"])
+    np.testing.assert_array_equal(orc.forward_bruteforce(*args, g["X"]), g["Y"])
+
+
+# ---- brute force on tiny ragged shapes: all evaluation orders agree ----
+@pytest.mark.parametrize("m,n,k,l", [(3, 5, 4, 1), (7, 6, 9, 2), (12, 11, 5, 3), (5, 33, 7, 4), (1, 1, 1, 1)])
+def test_bruteforce_equals_all_forms(m, n, k, l):
+    L, X = _tiny(10 + m + n, m, n, k, l)
+    ref = orc.forward_bruteforce(*_args(L), X)
+    for f in (orc.forward_dense, orc.forward_factored, orc.forward_sum_of_dbf):
+        np.testing.assert_allclose(f(*_args(L), X), ref, rtol=1e-11, atol=1e-11)
+
+
+# ---- l = 1 is plain DBF with m = q o g (Sec. 4.2, last paragraph; Eq. "dbf-basis") ----
+def test_l1_reduces_to_dbf():
+    L, X = _tiny(3, 17, 13, 21, 1)
+    a, q, g, b = (L[key][:, 0].astype(np.float64) for key in ("A", "Q", "G", "B"))
+    SAf = L["SA"].astype(np.float64)
+    SBf = L["SB"].astype(np.float64)
+    # Eq. "dbf-basis" written with explicit diagonal matrices
+    W_dbf = np.diag(a) @ SAf @ np.diag(q * g) @ SBf @ np.diag(b)
+    np.testing.assert_allclose(orc.dense_reconstruct(*_args(L)), W_dbf, rtol=1e-12, atol=1e-12)
+    Y_dbf = X.astype(np.float64) @ W_dbf.T
+    np.testing.assert_allclose(orc.forward_factored(*_args(L), X), Y_dbf, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(orc.dbf_forward(L["SA"], L["SB"], a, q * g, b, X), Y_dbf, rtol=1e-12, atol=1e-12)
+
+
+# ---- all-ones signs: What = (A Q^T)(G B^T), a plain rank-<=l product ----
+def test_all_plus_signs_give_lowrank_product():
+    L, X = _tiny(4, 9, 8, 10, 3)
+    L["SA"][:] = 1
+    L["SB"][:] = 1
+    W = (L["A"].astype(np.float64) @ L["Q"].T.astype(np.float64)) @ (
+        L["G"].astype(np.float64) @ L["B"].T.astype(np.float64))
+    np.testing.assert_allclose(orc.dense_reconstruct(*_args(L)), W, rtol=1e-12)
+    np.testing.assert_allclose(orc.forward_factored(*_args(L), X), X.astype(np.float64) @ W.T, rtol=1e-11, atol=1e-11)
+    assert np.linalg.matrix_rank(orc.dense_reconstruct(*_args(L))) <= 3
+
+
+# ---- all-ones envelopes, l = 1: What = SA SB, integers with the parity of k ----
+def test_unit_envelopes_give_integer_sign_product():
+    L = synth.make_layer(6, 7, 9, 1, seed=5, env_dtype="f32", env_kind="ones")
+    W = orc.dense_reconstruct(*_args(L))
+    Wi = L["SA"].astype(np.int64) @ L["SB"].astype(np.int64)
+    np.testing.assert_array_equal(W, Wi)
+    assert np.all(np.abs(Wi) <= 9) and np.all((Wi - 9) % 2 == 0)
+    # with l envelope modes that are all ones, What = l^2 SA SB
+    L4 = synth.make_layer(6, 7, 9, 4, seed=5, env_dtype="f32", env_kind="ones")
+    np.testing.assert_array_equal(orc.dense_reconstruct(*_args(L4)),
+                                  16 * (L4["SA"].astype(np.int64) @ L4["SB"].astype(np.int64)))
+
+
+# ---- demodulation identities (Eq. "me-dbf-envelope-rank"; S o (S o Z) = Z) ----
+def test_demodulated_envelope_rank_and_involution():
+    L, _ = _tiny(6, 20, 18, 16, 3)
+    U = orc.factor_U(L["SA"], L["A"], L["Q"])
+    V = orc.factor_V(L["SB"], L["G"], L["B"])
+    EU = orc.demodulate(L["SA"], U)
+    EV = orc.demodulate(L["SB"], V)
+    np.testing.assert_allclose(EU, L["A"].astype(np.float64) @ L["Q"].T, rtol=1e-12)
+    np.testing.assert_allclose(EV, L["G"].astype(np.float64) @ L["B"].T, rtol=1e-12)
+    for E in (EU, EV):
+        s = np.linalg.svd(E, compute_uv=False)
+        assert np.sum(s > 1e-9 * s[0]) <= 3
+    np.testing.assert_array_equal(orc.demodulate(L["SA"], EU), U)
+    # a sign-masked factor is generically full rank although its envelope is rank <= l
+    assert np.linalg.matrix_rank(U) > 3
+
+
+# ---- sign-mask isometry (Lemma "sign-invariance") ----
+def test_sign_mask_isometry():
+    rng = np.random.default_rng(7)
+    S = synth.random_signs(rng, 13, 9)
+    Z = rng.standard_normal((13, 9))
+    assert np.isclose(np.linalg.norm(orc.demodulate(S, Z)), np.linalg.norm(Z), rtol=1e-14)
+
+
+# ---- gauge invariances and linearity ----
+def test_gauge_and_linearity():
+    L, X = _tiny(8, 10, 12, 11, 3)
+    W = orc.dense_reconstruct(*_args(L))
+    # flipping column r of SA together with row r of SB leaves What unchanged
+    L2 = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in L.items()}
+    L2["SA"][:, 4] *= -1
+    L2["SB"][4, :] *= -1
+    np.testing.assert_allclose(orc.dense_reconstruct(*_args(L2)), W, rtol=1e-12, atol=1e-12)
+    # flipping only one of them changes it (the check above is not vacuous)
+    L3 = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in L.items()}
+    L3["SA"][:, 4] *= -1
+    assert not np.allclose(orc.dense_reconstruct(*_args(L3)), W)
+    # (A, Q) -> (A M, Q M^-T) leaves A Q^T, hence What, unchanged
+    rng = np.random.default_rng(9)
+    M = rng.standard_normal((3, 3)) + 3 * np.eye(3)
+    A2 = L["A"].astype(np.float64) @ M
+    Q2 = L["Q"].astype(np.float64) @ np.linalg.inv(M).T
+    np.testing.assert_allclose(orc.dense_reconstruct(L["SA"], L["SB"], A2, Q2, L["G"], L["B"]), W, rtol=1e-9, atol=1e-9)
+    # linear in x
+    Xd = X.astype(np.float64)
+    Y = orc.forward_factored(*_args(L), Xd)
+    Y2 = orc.forward_factored(*_args(L), 2.5 * Xd[:1] - 3.0 * Xd[1:2])
+    np.testing.assert_allclose(Y2[0], 2.5 * Y[0] - 3.0 * Y[1], rtol=1e-11, atol=1e-11)
+    # transposition symmetry: swapping the roles of the two factors transposes What
+    Wt = orc.dense_reconstruct(L["SB"].T, L["SA"].T, L["B"], L["G"], L["Q"], L["A"])
+    np.testing.assert_allclose(Wt, W.T, rtol=1e-12, atol=1e-12)
+
+
+# ---- a non-square layer keeps the operand orientations honest ----
+def test_rectangular_shapes_and_orientation():
+    L, X = _tiny(11, 5, 9, 4, 2)
+    Y = orc.forward_factored(*_args(L), X)
+    assert Y.shape == (2, 5)
+    W = orc.dense_reconstruct(*_args(L))
+    assert W.shape == (5, 9)
+    np.testing.assert_allclose(Y, X.astype(np.float64) @ W.T, rtol=1e-11, atol=1e-11)
+
+
+# ---- statistics: i.i.d. signs give E[y] = 0 and a closed-form variance ----
+def test_output_variance_closed_form():
+    m, n, k, l = 4, 6, 5, 2
+    rng = np.random.default_rng(12)
+    A = rng.standard_normal((m, l)); Q = rng.standard_normal((k, l))
+    G = rng.standard_normal((k, l)); B = rng.standard_normal((n, l))
+    x = rng.standard_normal((1, n))
+    EU = A @ Q.T
+    EV = G @ B.T
+    var = (EU ** 2) @ ((EV ** 2) @ (x[0] ** 2))
+    acc = np.zeros(m); acc2 = np.zeros(m)
+    N = 4000
+    for _ in range(N):
+        SA = synth.random_signs(rng, m, k); SB = synth.random_signs(rng, k, n)
+        y = orc.forward_factored(SA, SB, A, Q, G, B, x)[0]
+        acc += y; acc2 += y * y
+    mean = acc / N
+    v = acc2 / N
+    assert np.all(np.abs(mean) < 5 * np.sqrt(var / N))
+    np.testing.assert_allclose(v, var, rtol=0.15)
+
+
+# ---- bits per weight (Sec. 3.2 "Inference": bit-packed signs + real vectors over N*M) ----
+def test_bits_per_weight_closed_values():
+    assert orc.bits_per_weight(256, 256, 128, 4) == 1.75
+    assert orc.bits_per_weight(256, 256, 128, 4) == (65536 + 49152) / 65536
+    assert abs(orc.bits_per_weight(4096, 4096, 2656, 16) - 1.50293) < 5e-6
+    assert abs(orc.bits_per_weight(11008, 4096, 4096, 16) - 1.50436) < 5e-6
+    assert orc.bits_per_weight(11008, 4096, 4096, 16) == orc.bits_per_weight(4096, 11008, 4096, 16)
+    # plain DBF count: signs + {a, b, m}
+    m, n, k = 64, 48, 32
+    assert orc.bits_per_weight(m, n, k, 1, merge_inner=True) == ((m + n) * k + 16 * (m + n + k)) / (m * n)
+    # keeping q and g apart costs exactly 16 k more bits
+    d = orc.bits_per_weight(m, n, k, 1) - orc.bits_per_weight(m, n, k, 1, merge_inner=True)
+    assert abs(d - 16 * k / (m * n)) < 1e-15
+    with pytest.raises(ValueError):
+        orc.bits_per_weight(m, n, k, 2, merge_inner=True)
+
+
+def test_rank_for_budget():
+    # strict rule: the largest rank that meets the budget (Sec. 5.1)
+    for (m, n, l, bpw) in [(4096, 4096, 16, 1.5), (11008, 4096, 16, 1.5), (4096, 4096, 8, 1.0), (512, 384, 2, 1.25)]:
+        k = orc.rank_for_budget(m, n, l, bpw)
+        assert orc.bits_per_weight(m, n, k, l) <= bpw < orc.bits_per_weight(m, n, k + 1, l)
+    assert orc.rank_for_budget(4096, 4096, 16, 1.5) == 2650
+    assert orc.rank_for_budget(11008, 4096, 16, 1.5) == 4083
+    # word-aligned rule reproduces the benchmark ranks
+    assert orc.rank_for_budget(4096, 4096, 16, 1.5, multiple=32) == 2656
+    assert orc.rank_for_budget(11008, 4096, 16, 1.5, multiple=32) == 4096
+    assert orc.rank_for_budget(4096, 4096, 8, 1.0, multiple=32) == 1856
+    assert orc.rank_for_budget(11008, 4096, 8, 1.0, multiple=32) == 2816
+    assert orc.rank_for_budget(4096, 4096, 16, 2.0, multiple=32) == 3616
+    assert orc.rank_for_budget(11008, 4096, 16, 2.0, multiple=32) == 5536
+
+
+# ---- sign convention and the reference bit layout ----
+def test_sign_of_zero_is_plus_one():
+    s = orc.sign_pm1(np.array([[-2.0, -0.0, 0.0, 3.0]]))
+    np.testing.assert_array_equal(s, [[-1, 1, 1, 1]])
+
+
+def test_pack_ref_layout_and_roundtrip():
+    S = np.ones((2, 40), dtype=np.int8)
+    S[0, 0] = -1      # word 0 bit 0
+    S[0, 33] = -1     # word 1 bit 1
+    S[1, 31] = -1     # word 0 bit 31
+    P = orc.pack_ref(S)
+    assert P.shape == (2, 2) and P.dtype == np.uint32
+    np.testing.assert_array_equal(P, np.array([[1, 2], [0x80000000, 0]], dtype=np.uint32))
+    rng = np.random.default_rng(3)
+    for rows, cols in [(1, 1), (5, 31), (4, 32), (3, 33), (7, 100)]:
+        S = synth.random_signs(rng, rows, cols)
+        np.testing.assert_array_equal(orc.unpack_ref(orc.pack_ref(S), cols), S)
+        # little-endian byte view agrees with numpy's own bit packer
+        ref = np.packbits((S < 0).astype(np.uint8), axis=1, bitorder="little")
+        got = orc.pack_ref(S).view(np.uint8)[:, : ref.shape[1]]
+        np.testing.assert_array_equal(got, ref)
+
+
+# ---- the pins notice planted mistakes (mistakes planted in copies of the oracle, on the CPU) ----
+def test_pins_detect_planted_mistakes(golden_tiny):
+    g = golden_tiny
+    SA, SB = g["SA"], g["SB"]
+    A, Q, G, B, X = g["A"], g["Q"], g["G"], g["B"], g["X"]
+    good = g["Y"]
+    # transposed right sign basis
+    bad1 = X @ ((SA * (A @ Q.T)) @ (SB.T * (G @ B.T))).T
+    # envelope factors of the right factor swapped
+    bad2 = X @ ((SA * (A @ Q.T)) @ (SB * (B @ G.T))).T
+    # missing inner re-scale
+    bad3 = X @ ((SA * (A @ np.ones_like(Q).T)) @ (SB * (G @ B.T))).T
+    for bad in (bad1, bad2, bad3):
+        assert not np.allclose(bad, good)
+
+
+def test_max_rel_error_definition():
+    Y = np.array([[1.0, -4.0, 2.0]])
+    assert orc.max_rel_error(Y + np.array([[0.0, 0.0, 0.02]]), Y) == pytest.approx(0.005)
