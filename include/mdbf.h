@@ -1,0 +1,162 @@
+/*
+ * mdbf.h -- C ABI of the MI355X (gfx950) forward product for Multi-Envelope
+ * Double Binary Factorization (MDBF).
+ *
+ * The format (paper Sec. 4.2, Eq. "me-dbf-basis"): a weight matrix W (m x n) is
+ * replaced by
+ *        What = U V,   U = SA o (A Q^T)  (m x k),   V = SB o (G B^T)  (k x n)
+ * with shared sign bases SA in {+-1}^{m x k}, SB in {+-1}^{k x n} (SB is the
+ * paper's S_b transposed), rank-l real envelope factors A (m x l), Q (k x l),
+ * G (k x l), B (n x l), and `o` the Hadamard product.  In the paper's symbols
+ * m = N, n = M, k = R.
+ *
+ * The operation (paper Sec. 3.2 "Inference", generalised through the per-factor
+ * expansion of Eq. "me-dbf-expand"): for every token b
+ *        Y[b,:] = What X[b,:]
+ * evaluated as two envelope-scaled binary products,
+ *        z = sum_s g^(s) o ( SB (b^(s) o x) ),    y = sum_t a^(t) o ( SA (q^(t) o z) ).
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller; the library
+ *    never allocates, frees or keeps device memory.  Everything else is host memory.
+ *  - All launches are asynchronous on `stream` (a hipStream_t passed as void*;
+ *    NULL is the default stream).  No call synchronises or reads device memory on
+ *    the host, so the forward calls can be captured into a HIP graph.
+ *  - Every function returns 0 (MDBF_OK) or a negative mdbf_status; arguments are
+ *    validated before the first HIP call, so bad arguments are reported on hosts
+ *    without a GPU as well.
+ *  - Device pointers must be 16-byte aligned.
+ */
+#ifndef MDBF_H
+#define MDBF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MDBF_VERSION 100
+#define MDBF_MAX_L 16          /* envelope rank supported: 1..16 (the paper sweeps l in {1,2,3,8,16}) */
+
+typedef enum {
+  MDBF_OK = 0,
+  MDBF_EINVAL = -1,        /* null pointer, non-positive shape, l out of range, T < 1, bad leading dimension */
+  MDBF_EALIGN = -2,        /* a device pointer is not 16-byte aligned */
+  MDBF_EDTYPE = -3,        /* unknown dtype code */
+  MDBF_EWORKSPACE = -4,    /* workspace / output buffer too small */
+  MDBF_EUNSUPPORTED = -5,  /* valid request this build cannot serve */
+  MDBF_EHIP = -6           /* a HIP call failed; mdbf_last_hip_error() gives the text */
+} mdbf_status;
+
+typedef enum { MDBF_F16 = 0, MDBF_BF16 = 1, MDBF_F32 = 2 } mdbf_dtype;
+
+/* flags of mdbf_desc_t */
+#define MDBF_FLAG_PRECISE 1u   /* fp32 vector arithmetic throughout (no fp16 staging, no matrix cores); slow */
+
+typedef struct {
+  int32_t m, n, k, l;      /* What is m x n, inner rank k, envelope rank l */
+  int32_t x_dtype;         /* dtype of X            (mdbf_dtype) */
+  int32_t env_dtype;       /* dtype of A, Q, G, B   (mdbf_dtype) */
+  int32_t y_dtype;         /* dtype of Y            (mdbf_dtype) */
+  uint32_t flags;
+} mdbf_desc_t;
+
+/* Envelope factors, row-major with the l modes of one row contiguous (the paper's
+ * A = [a^(1) ... a^(l)] stored as m rows of l values). */
+typedef struct {
+  const void* A_dev;  /* m x l */
+  const void* Q_dev;  /* k x l */
+  const void* G_dev;  /* k x l */
+  const void* B_dev;  /* n x l */
+} mdbf_env_t;
+
+/* ---- storage accounting (host only) ------------------------------------------------
+ * Bits per weight: bit-packed signs plus the real envelope entries over the m*n entries
+ * replaced (paper Sec. 3.2, last sentence of "Inference", applied to the factors listed
+ * under Eq. "me-dbf-basis"):  [ (m+n)k + env_bits*l*(m+n+2k) ] / (mn).
+ * merge_inner != 0 (only with l == 1) counts q o g as one vector, the plain DBF count.
+ * Returns a negative value on invalid arguments. */
+double mdbf_bpw(int m, int n, int k, int l, int env_bits, int merge_inner);
+
+/* Inner rank for a bits-per-weight budget (paper Sec. 5.1, "largest inner rank that meets
+ * the budget").  multiple <= 1: the largest k with mdbf_bpw <= bpw.  multiple > 1: the real
+ * solution of mdbf_bpw(k) = bpw rounded to the nearest multiple (word-aligned ranks).
+ * Returns k >= 0, or a negative mdbf_status. */
+int mdbf_rank_for_budget(int m, int n, int l, double bpw, int env_bits, int multiple);
+
+/* ---- sign bit-packing ("bit-packed sign matrices", paper Sec. 1 and Sec. 3.2) -------------
+ * A sign matrix S (rows x cols) is contracted along `cols` in the forward product: for SA
+ * rows = m, cols = k; for SB rows = k, cols = n.  One bit per entry, bit 1 <=> -1, in a
+ * device tile layout private to this library (16-row tiles, 128-column blocks, padding bits 0).
+ * mdbf_packed_bytes: size in bytes of the packed blob (host only). */
+int mdbf_packed_bytes(int rows, int cols, size_t* bytes_out);
+
+/* signs_dev: rows x cols int8, row-major with leading dimension ld >= cols; an entry < 0
+ * packs as -1, an entry >= 0 as +1 (sign(0) = +1, paper Sec. 2).  packed_dev must hold
+ * mdbf_packed_bytes(rows, cols) bytes (packed_bytes is checked) and is fully overwritten. */
+int mdbf_pack(const int8_t* signs_dev, int rows, int cols, int64_t ld,
+              void* packed_dev, size_t packed_bytes, void* stream);
+
+/* Inverse of mdbf_pack: writes +1 / -1 into signs_dev (rows x cols int8, leading dim ld). */
+int mdbf_unpack(const void* packed_dev, int rows, int cols,
+                int8_t* signs_dev, int64_t ld, void* stream);
+
+/* ---- forward product ------------------------------------------------------------------
+ * Workspace bytes needed by mdbf_forward for T tokens (holds the inner vector z, fp32). */
+int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out);
+
+/* Y[b,:] = What X[b,:] for b < T.
+ *   SA_packed_dev  packed SA (m x k),  SB_packed_dev  packed SB (k x n)
+ *   X_dev  T x n row-major, leading dimension ldx >= n (elements of x_dtype)
+ *   Y_dev  T x m row-major, leading dimension ldy >= m (elements of y_dtype); overwritten
+ *   workspace_dev / workspace_bytes  caller-owned scratch, >= mdbf_workspace_bytes()
+ * Default arithmetic: the l-way scaled activations (b^(s) o x and q^(t) o z) are rounded to
+ * fp16 once, sign words are expanded in registers and contracted on the matrix cores with
+ * fp32 accumulation; z is kept in fp32.  Values of |b o x| or |q o z| above 65504 overflow.
+ * With MDBF_FLAG_PRECISE everything is fp32 vector arithmetic. */
+int mdbf_forward(const mdbf_desc_t* desc,
+                 const void* SA_packed_dev, const void* SB_packed_dev,
+                 const mdbf_env_t* env,
+                 const void* X_dev, int64_t ldx,
+                 void* Y_dev, int64_t ldy, int T,
+                 void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* ---- many independent layers in one pair of launches -----------------------------------
+ * One entry per layer; the same meaning as the arguments of mdbf_forward.  Serves sibling
+ * projections and whole stacks of independent products with two kernel launches in total. */
+typedef struct {
+  mdbf_desc_t desc;
+  const void* SA_packed_dev;
+  const void* SB_packed_dev;
+  mdbf_env_t env;
+  const void* X_dev;
+  int64_t ldx;
+  void* Y_dev;
+  int64_t ldy;
+  int32_t T;
+} mdbf_layer_t;
+
+/* Sizes of the plan (a table the kernels read) and of the device workspace for `count` layers. */
+int mdbf_batch_plan_bytes(int count, const mdbf_layer_t* layers, size_t* plan_bytes_out,
+                          size_t* workspace_bytes_out);
+
+/* Fills plan_host (plan_bytes from mdbf_batch_plan_bytes) for the given layers and workspace
+ * address.  The caller copies the plan verbatim to device memory (plan_dev) before calling
+ * mdbf_forward_batch and keeps plan_host alive: the host reads launch sizes from it. */
+int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace_dev,
+                          size_t workspace_bytes, void* plan_host, size_t plan_bytes);
+
+/* Runs all layers of a plan.  Asynchronous on `stream`, no allocation, no host-device copy. */
+int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream);
+
+/* ---- misc ----------------------------------------------------------------------------- */
+const char* mdbf_strerror(int status);
+const char* mdbf_last_hip_error(void);   /* text of the last failed HIP call on this thread, or "" */
+int mdbf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MDBF_H */

@@ -1,0 +1,240 @@
+"""ctypes binding of libmdbf.so: argument marshalling only.
+
+PyTorch supplies device memory and streams; every step of the forward product runs in
+the library's HIP kernels.  There is no CPU or PyTorch fallback: if the library cannot
+be loaded (and cannot be built), importing callers get an exception.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+MDBF_F16, MDBF_BF16, MDBF_F32 = 0, 1, 2
+MDBF_FLAG_PRECISE = 1
+DTYPE_CODE = {"f16": MDBF_F16, "bf16": MDBF_BF16, "f32": MDBF_F32}
+
+STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE", -4: "MDBF_EWORKSPACE",
+          -5: "MDBF_EUNSUPPORTED", -6: "MDBF_EHIP"}
+
+EXPORTS = [
+    "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack",
+    "mdbf_workspace_bytes", "mdbf_forward", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
+    "mdbf_forward_batch", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
+]
+
+
+class MdbfError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = "%s failed: %s (%d)" % (where, STATUS.get(status, "?"), status)
+        if status == -6:
+            msg += ": " + lib().mdbf_last_hip_error().decode()
+        super().__init__(msg)
+
+
+class Desc(C.Structure):
+    _fields_ = [("m", C.c_int32), ("n", C.c_int32), ("k", C.c_int32), ("l", C.c_int32),
+                ("x_dtype", C.c_int32), ("env_dtype", C.c_int32), ("y_dtype", C.c_int32),
+                ("flags", C.c_uint32)]
+
+
+class Env(C.Structure):
+    _fields_ = [("A_dev", C.c_void_p), ("Q_dev", C.c_void_p), ("G_dev", C.c_void_p), ("B_dev", C.c_void_p)]
+
+
+class Layer(C.Structure):
+    _fields_ = [("desc", Desc), ("SA_packed_dev", C.c_void_p), ("SB_packed_dev", C.c_void_p), ("env", Env),
+                ("X_dev", C.c_void_p), ("ldx", C.c_int64), ("Y_dev", C.c_void_p), ("ldy", C.c_int64),
+                ("T", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libmdbf.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_library()
+    L = C.CDLL(_build.LIB_PATH)
+    L.mdbf_bpw.restype = C.c_double
+    L.mdbf_bpw.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
+    L.mdbf_rank_for_budget.restype = C.c_int
+    L.mdbf_rank_for_budget.argtypes = [C.c_int, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int]
+    L.mdbf_packed_bytes.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    L.mdbf_pack.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.mdbf_unpack.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+    L.mdbf_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int, C.POINTER(C.c_size_t)]
+    L.mdbf_forward.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.POINTER(Env), C.c_void_p, C.c_int64,
+                               C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.mdbf_batch_plan_bytes.argtypes = [C.c_int, C.POINTER(Layer), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+    L.mdbf_batch_plan_build.argtypes = [C.c_int, C.POINTER(Layer), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]
+    L.mdbf_forward_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.mdbf_strerror.restype = C.c_char_p
+    L.mdbf_strerror.argtypes = [C.c_int]
+    L.mdbf_last_hip_error.restype = C.c_char_p
+    L.mdbf_version.restype = C.c_int
+    for name in EXPORTS:
+        getattr(L, name)
+    _lib = L
+    return L
+
+
+def _check(status, where):
+    if status != 0:
+        raise MdbfError(status, where)
+
+
+# ---- host-only calls ------------------------------------------------------------------------
+def mdbf_bpw(m, n, k, l, env_bits=16, merge_inner=False):
+    return lib().mdbf_bpw(m, n, k, l, env_bits, int(merge_inner))
+
+
+def mdbf_rank_for_budget(m, n, l, bpw, env_bits=16, multiple=1):
+    return lib().mdbf_rank_for_budget(m, n, l, float(bpw), env_bits, multiple)
+
+
+def mdbf_packed_bytes(rows, cols):
+    out = C.c_size_t(0)
+    _check(lib().mdbf_packed_bytes(rows, cols, C.byref(out)), "mdbf_packed_bytes")
+    return out.value
+
+
+def mdbf_version():
+    return lib().mdbf_version()
+
+
+# ---- device calls (torch tensors carry the device memory) -----------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _stream_ptr(stream=None):
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _torch_dtype(name):
+    torch = _torch()
+    return {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[name]
+
+
+def _dtype_name(t):
+    torch = _torch()
+    return {torch.float16: "f16", torch.bfloat16: "bf16", torch.float32: "f32"}[t.dtype]
+
+
+def mdbf_pack(signs, stream=None):
+    """signs: int8 CUDA tensor (rows, cols), entries +-1 (>= 0 packs as +1).  Returns a uint8 CUDA tensor."""
+    torch = _torch()
+    assert signs.is_cuda and signs.dtype == torch.int8 and signs.dim() == 2 and signs.stride(1) == 1
+    rows, cols = signs.shape
+    nbytes = mdbf_packed_bytes(rows, cols)
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=signs.device)
+    _check(lib().mdbf_pack(signs.data_ptr(), rows, cols, signs.stride(0), packed.data_ptr(), nbytes,
+                           _stream_ptr(stream)), "mdbf_pack")
+    return packed
+
+
+def mdbf_unpack(packed, rows, cols, stream=None):
+    torch = _torch()
+    out = torch.empty((rows, cols), dtype=torch.int8, device=packed.device)
+    _check(lib().mdbf_unpack(packed.data_ptr(), rows, cols, out.data_ptr(), out.stride(0), _stream_ptr(stream)),
+           "mdbf_unpack")
+    return out
+
+
+class DeviceLayer:
+    """Device-resident MDBF layer: packed sign bases and envelope factors."""
+
+    def __init__(self, m, n, k, l, SA_packed, SB_packed, A, Q, G, B):
+        self.m, self.n, self.k, self.l = m, n, k, l
+        self.SA_packed, self.SB_packed = SA_packed, SB_packed
+        self.A, self.Q, self.G, self.B = A, Q, G, B
+        self.env_dtype = _dtype_name(A)
+
+    @staticmethod
+    def from_host(layer, device="cuda:0"):
+        """layer: dict from synth.make_layer (numpy).  Uploads, then packs the signs on the GPU."""
+        torch = _torch()
+        dt = _torch_dtype(layer["env_dtype"])
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+        SA = mdbf_pack(up(layer["SA"]))
+        SB = mdbf_pack(up(layer["SB"]))
+        env = [up(layer[kname]).to(dt).contiguous() for kname in ("A", "Q", "G", "B")]
+        return DeviceLayer(layer["m"], layer["n"], layer["k"], layer["l"], SA, SB, *env)
+
+    def desc(self, x_dtype, y_dtype, precise=False):
+        return Desc(self.m, self.n, self.k, self.l, DTYPE_CODE[x_dtype], DTYPE_CODE[self.env_dtype],
+                    DTYPE_CODE[y_dtype], MDBF_FLAG_PRECISE if precise else 0)
+
+    def env(self):
+        return Env(self.A.data_ptr(), self.Q.data_ptr(), self.G.data_ptr(), self.B.data_ptr())
+
+
+def mdbf_workspace_bytes(desc, T):
+    out = C.c_size_t(0)
+    _check(lib().mdbf_workspace_bytes(C.byref(desc), T, C.byref(out)), "mdbf_workspace_bytes")
+    return out.value
+
+
+def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None, stream=None):
+    """Y[b,:] = What X[b,:].  X: CUDA tensor (T, n) of f16/bf16/f32; returns Y (T, m) of y_dtype."""
+    torch = _torch()
+    assert X.is_cuda and X.dim() == 2 and X.shape[1] == layer.n and X.stride(1) == 1
+    T = X.shape[0]
+    d = layer.desc(_dtype_name(X), y_dtype, precise)
+    if Y is None:
+        Y = torch.empty((T, layer.m), dtype=_torch_dtype(y_dtype), device=X.device)
+    if workspace is None:
+        workspace = torch.empty(mdbf_workspace_bytes(d, T), dtype=torch.uint8, device=X.device)
+    env = layer.env()
+    _check(lib().mdbf_forward(C.byref(d), layer.SA_packed.data_ptr(), layer.SB_packed.data_ptr(), C.byref(env),
+                              X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), T, workspace.data_ptr(),
+                              workspace.numel(), _stream_ptr(stream)), "mdbf_forward")
+    return Y
+
+
+class BatchPlan:
+    """Plan for many independent layers: two launches for all of them."""
+
+    def __init__(self, layers, Xs, Ys, precise=False):
+        torch = _torch()
+        assert len(layers) == len(Xs) == len(Ys) and len(layers) > 0
+        n = len(layers)
+        arr = (Layer * n)()
+        for i, (L, X, Y) in enumerate(zip(layers, Xs, Ys)):
+            arr[i].desc = L.desc(_dtype_name(X), _dtype_name(Y), precise)
+            arr[i].SA_packed_dev = L.SA_packed.data_ptr()
+            arr[i].SB_packed_dev = L.SB_packed.data_ptr()
+            arr[i].env = L.env()
+            arr[i].X_dev = X.data_ptr()
+            arr[i].ldx = X.stride(0)
+            arr[i].Y_dev = Y.data_ptr()
+            arr[i].ldy = Y.stride(0)
+            arr[i].T = X.shape[0]
+        pb, wb = C.c_size_t(0), C.c_size_t(0)
+        _check(lib().mdbf_batch_plan_bytes(n, arr, C.byref(pb), C.byref(wb)), "mdbf_batch_plan_bytes")
+        self.keep = (layers, Xs, Ys)
+        self.workspace = torch.empty(max(wb.value, 16), dtype=torch.uint8, device=Xs[0].device)
+        self.plan_host = torch.empty(pb.value, dtype=torch.uint8)
+        _check(lib().mdbf_batch_plan_build(n, arr, self.workspace.data_ptr(), self.workspace.numel(),
+                                           self.plan_host.data_ptr(), pb.value), "mdbf_batch_plan_build")
+        self.plan_dev = self.plan_host.to(Xs[0].device)
+        self.plan_bytes = pb.value
+
+    def run(self, stream=None):
+        _check(lib().mdbf_forward_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), self.plan_bytes,
+                                        _stream_ptr(stream)), "mdbf_forward_batch")
+
+
+def mdbf_forward_batch(plan, stream=None):
+    plan.run(stream)

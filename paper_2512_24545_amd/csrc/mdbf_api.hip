@@ -1,0 +1,308 @@
+// C ABI of libmdbf: argument validation, storage accounting, plans and kernel dispatch.
+// Every argument check happens before the first HIP call.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "mdbf_internal.h"
+
+using namespace mdbf;
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int hip_fail(int e) {
+  if (e == 0) return MDBF_OK;
+  snprintf(g_hip_err, sizeof(g_hip_err), "%s", hipGetErrorString((hipError_t)e));
+  return MDBF_EHIP;
+}
+
+bool valid_dtype(int d) { return d == MDBF_F16 || d == MDBF_BF16 || d == MDBF_F32; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+int kpad_of(int k) { return (k + 3) & ~3; }  // z rows are 16-byte aligned
+
+int check_desc(const mdbf_desc_t* d) {
+  if (!d) return MDBF_EINVAL;
+  if (d->m <= 0 || d->n <= 0 || d->k <= 0) return MDBF_EINVAL;
+  if (d->l < 1 || d->l > MDBF_MAX_L) return MDBF_EINVAL;
+  if (!valid_dtype(d->x_dtype) || !valid_dtype(d->env_dtype) || !valid_dtype(d->y_dtype)) return MDBF_EDTYPE;
+  if (d->flags & ~MDBF_FLAG_PRECISE) return MDBF_EUNSUPPORTED;
+  return MDBF_OK;
+}
+
+size_t z_bytes(const mdbf_desc_t* d, int T) { return align_up((size_t)T * (size_t)kpad_of(d->k) * 4u, 256); }
+
+int check_layer(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
+                int64_t ldx, void* Y, int64_t ldy, int T) {
+  int st = check_desc(d);
+  if (st) return st;
+  if (!SA || !SB || !env || !X || !Y) return MDBF_EINVAL;
+  if (!env->A_dev || !env->Q_dev || !env->G_dev || !env->B_dev) return MDBF_EINVAL;
+  if (T < 1) return MDBF_EINVAL;
+  if (ldx < d->n || ldy < d->m) return MDBF_EINVAL;
+  if (!aligned16(SA) || !aligned16(SB) || !aligned16(X) || !aligned16(Y) || !aligned16(env->A_dev) ||
+      !aligned16(env->Q_dev) || !aligned16(env->G_dev) || !aligned16(env->B_dev))
+    return MDBF_EALIGN;
+  return MDBF_OK;
+}
+
+// the two stage problems of one layer (paper Eq. "me-dbf-expand": V first, then U)
+void make_stages(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
+                 int64_t ldx, void* Y, int64_t ldy, int T, void* z, StageProb out[2]) {
+  StageProb s1;
+  memset(&s1, 0, sizeof(s1));
+  s1.S = (const uint32_t*)SB;
+  s1.Ein = env->B_dev;
+  s1.Eout = env->G_dev;
+  s1.vin = X;
+  s1.out = z;
+  s1.vin_ld = ldx;
+  s1.out_ld = kpad_of(d->k);
+  s1.rows = d->k;
+  s1.K = d->n;
+  s1.l = d->l;
+  s1.T = T;
+  s1.KB = num_blocks(d->n);
+  s1.ntiles = num_tiles(d->k);
+  s1.env_dt = d->env_dtype;
+  s1.vin_dt = d->x_dtype;
+  s1.out_dt = MDBF_F32;
+  StageProb s2;
+  memset(&s2, 0, sizeof(s2));
+  s2.S = (const uint32_t*)SA;
+  s2.Ein = env->Q_dev;
+  s2.Eout = env->A_dev;
+  s2.vin = z;
+  s2.out = Y;
+  s2.vin_ld = kpad_of(d->k);
+  s2.out_ld = ldy;
+  s2.rows = d->m;
+  s2.K = d->k;
+  s2.l = d->l;
+  s2.T = T;
+  s2.KB = num_blocks(d->k);
+  s2.ntiles = num_tiles(d->m);
+  s2.env_dt = d->env_dtype;
+  s2.vin_dt = MDBF_F32;
+  s2.out_dt = d->y_dtype;
+  out[0] = s1;
+  out[1] = s2;
+}
+
+}  // namespace
+
+extern "C" {
+
+double mdbf_bpw(int m, int n, int k, int l, int env_bits, int merge_inner) {
+  if (m <= 0 || n <= 0 || k <= 0 || l < 1 || env_bits < 1) return -1.0;
+  if (merge_inner && l != 1) return -1.0;
+  const double sign_bits = ((double)m + (double)n) * (double)k;
+  const double real_entries = merge_inner ? ((double)m + n + k) : (double)l * ((double)m + n + 2.0 * k);
+  return (sign_bits + (double)env_bits * real_entries) / ((double)m * (double)n);
+}
+
+int mdbf_rank_for_budget(int m, int n, int l, double bpw, int env_bits, int multiple) {
+  if (m <= 0 || n <= 0 || l < 1 || env_bits < 1 || !(bpw > 0.0)) return MDBF_EINVAL;
+  const double mn = (double)m * (double)n, s = (double)m + (double)n;
+  const double k_real = (bpw * mn - (double)env_bits * l * s) / (s + 2.0 * env_bits * l);
+  if (k_real < 0.0) return 0;
+  if (multiple <= 1) {
+    long k = (long)floor(k_real + 1e-9);
+    while (k > 0 && mdbf_bpw(m, n, (int)k, l, env_bits, 0) > bpw + 1e-12) --k;
+    while (mdbf_bpw(m, n, (int)k + 1, l, env_bits, 0) <= bpw + 1e-12) ++k;
+    return (int)k;
+  }
+  return (int)(multiple * floor(k_real / multiple + 0.5));
+}
+
+int mdbf_packed_bytes(int rows, int cols, size_t* bytes_out) {
+  if (!bytes_out || rows <= 0 || cols <= 0) return MDBF_EINVAL;
+  *bytes_out = packed_words(rows, cols) * 4u;
+  return MDBF_OK;
+}
+
+int mdbf_pack(const int8_t* signs_dev, int rows, int cols, int64_t ld, void* packed_dev, size_t packed_bytes,
+              void* stream) {
+  if (!signs_dev || !packed_dev || rows <= 0 || cols <= 0 || ld < cols) return MDBF_EINVAL;
+  if (!aligned16(packed_dev)) return MDBF_EALIGN;
+  if (packed_bytes < packed_words(rows, cols) * 4u) return MDBF_EWORKSPACE;
+  return hip_fail(launch_pack(signs_dev, rows, cols, ld, (uint32_t*)packed_dev, (hipStream_t)stream));
+}
+
+int mdbf_unpack(const void* packed_dev, int rows, int cols, int8_t* signs_dev, int64_t ld, void* stream) {
+  if (!signs_dev || !packed_dev || rows <= 0 || cols <= 0 || ld < cols) return MDBF_EINVAL;
+  if (!aligned16(packed_dev)) return MDBF_EALIGN;
+  return hip_fail(launch_unpack((const uint32_t*)packed_dev, rows, cols, signs_dev, ld, (hipStream_t)stream));
+}
+
+int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out) {
+  int st = check_desc(desc);
+  if (st) return st;
+  if (!bytes_out || T < 1) return MDBF_EINVAL;
+  *bytes_out = z_bytes(desc, T);
+  return MDBF_OK;
+}
+
+int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void* SB_packed_dev,
+                 const mdbf_env_t* env, const void* X_dev, int64_t ldx, void* Y_dev, int64_t ldy, int T,
+                 void* workspace_dev, size_t workspace_bytes, void* stream) {
+  int st = check_layer(desc, SA_packed_dev, SB_packed_dev, env, X_dev, ldx, Y_dev, ldy, T);
+  if (st) return st;
+  if (!workspace_dev) return MDBF_EINVAL;
+  if (!aligned16(workspace_dev)) return MDBF_EALIGN;
+  if (workspace_bytes < z_bytes(desc, T)) return MDBF_EWORKSPACE;
+  StageProb sp[2];
+  make_stages(desc, SA_packed_dev, SB_packed_dev, env, X_dev, ldx, Y_dev, ldy, T, workspace_dev, sp);
+  hipStream_t s = (hipStream_t)stream;
+  for (int i = 0; i < 2; ++i) {
+    int e;
+    if (desc->flags & MDBF_FLAG_PRECISE)
+      e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
+    else
+      e = launch_stage_mfma(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], s);
+    if (e) return hip_fail(e);
+  }
+  return MDBF_OK;
+}
+
+static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, size_t* ws_bytes) {
+  if (count < 1 || !layers) return MDBF_EINVAL;
+  long tiles[2] = {0, 0};
+  size_t ws = 0;
+  int precise = 0;
+  for (int i = 0; i < count; ++i) {
+    const mdbf_layer_t* L = &layers[i];
+    int st = check_layer(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev,
+                         L->ldy, L->T);
+    if (st) return st;
+    precise += (L->desc.flags & MDBF_FLAG_PRECISE) ? 1 : 0;
+    tiles[0] += num_tiles(L->desc.k);
+    tiles[1] += num_tiles(L->desc.m);
+    ws += z_bytes(&L->desc, L->T);
+  }
+  if (precise != 0 && precise != count) return MDBF_EUNSUPPORTED;  // all or none
+  memset(h, 0, sizeof(*h));
+  h->magic = kPlanMagic;
+  h->count = count;
+  h->precise = precise ? 1 : 0;
+  // one tile count per work item for both stages keeps one kernel instantiation per plan
+  const int tpi = mfma_tiles_per_item(tiles[0] < tiles[1] ? tiles[0] : tiles[1]);
+  h->tiles_per_item = tpi;
+  long nitems[2] = {0, 0};
+  for (int i = 0; i < count; ++i) {
+    nitems[0] += (num_tiles(layers[i].desc.k) + tpi - 1) / tpi;
+    nitems[1] += (num_tiles(layers[i].desc.m) + tpi - 1) / tpi;
+  }
+  if (nitems[0] > 65535 || nitems[1] > 65535) return MDBF_EUNSUPPORTED;
+  h->nitems[0] = (int)nitems[0];
+  h->nitems[1] = (int)nitems[1];
+  size_t off = align_up(sizeof(PlanHeader), 256);
+  for (int s = 0; s < 2; ++s) {
+    h->probs_off[s] = off;
+    off = align_up(off + (size_t)count * sizeof(StageProb), 256);
+  }
+  for (int s = 0; s < 2; ++s) {
+    h->items_off[s] = off;
+    off = align_up(off + (size_t)nitems[s] * sizeof(WorkItem), 256);
+  }
+  h->total_bytes = off;
+  *ws_bytes = ws;
+  return MDBF_OK;
+}
+
+int mdbf_batch_plan_bytes(int count, const mdbf_layer_t* layers, size_t* plan_bytes_out,
+                          size_t* workspace_bytes_out) {
+  if (!plan_bytes_out || !workspace_bytes_out) return MDBF_EINVAL;
+  PlanHeader h;
+  size_t ws;
+  int st = batch_layout(count, layers, &h, &ws);
+  if (st) return st;
+  *plan_bytes_out = (size_t)h.total_bytes;
+  *workspace_bytes_out = ws;
+  return MDBF_OK;
+}
+
+int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace_dev, size_t workspace_bytes,
+                          void* plan_host, size_t plan_bytes) {
+  if (!plan_host || !workspace_dev) return MDBF_EINVAL;
+  if (!aligned16(workspace_dev)) return MDBF_EALIGN;
+  PlanHeader h;
+  size_t ws;
+  int st = batch_layout(count, layers, &h, &ws);
+  if (st) return st;
+  if (plan_bytes < h.total_bytes || workspace_bytes < ws) return MDBF_EWORKSPACE;
+  unsigned char* base = (unsigned char*)plan_host;
+  memset(base, 0, (size_t)h.total_bytes);
+  memcpy(base, &h, sizeof(h));
+  StageProb* probs[2] = {(StageProb*)(base + h.probs_off[0]), (StageProb*)(base + h.probs_off[1])};
+  WorkItem* items[2] = {(WorkItem*)(base + h.items_off[0]), (WorkItem*)(base + h.items_off[1])};
+  size_t zoff = 0;
+  int ni[2] = {0, 0};
+  const int tpi = h.tiles_per_item;
+  for (int i = 0; i < count; ++i) {
+    const mdbf_layer_t* L = &layers[i];
+    StageProb sp[2];
+    make_stages(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev, L->ldy, L->T,
+                (unsigned char*)workspace_dev + zoff, sp);
+    zoff += z_bytes(&L->desc, L->T);
+    for (int s = 0; s < 2; ++s) {
+      probs[s][i] = sp[s];
+      for (int t0 = 0; t0 < sp[s].ntiles; t0 += tpi) {
+        WorkItem w;
+        w.prob = i;
+        w.tile0 = t0;
+        w.ntiles = sp[s].ntiles - t0 < tpi ? sp[s].ntiles - t0 : tpi;
+        w.pad_ = 0;
+        items[s][ni[s]++] = w;
+      }
+    }
+  }
+  return MDBF_OK;
+}
+
+int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream) {
+  if (!plan_host || !plan_dev) return MDBF_EINVAL;
+  if (!aligned16(plan_dev)) return MDBF_EALIGN;
+  PlanHeader h;
+  if (plan_bytes < sizeof(PlanHeader)) return MDBF_EWORKSPACE;
+  memcpy(&h, plan_host, sizeof(h));
+  if (h.magic != kPlanMagic || h.count < 1 || h.total_bytes > plan_bytes) return MDBF_EINVAL;
+  const unsigned char* dev = (const unsigned char*)plan_dev;
+  hipStream_t s = (hipStream_t)stream;
+  for (int st = 0; st < 2; ++st) {
+    const StageProb* probs = (const StageProb*)(dev + h.probs_off[st]);
+    const WorkItem* items = (const WorkItem*)(dev + h.items_off[st]);
+    StageProb dummy;
+    memset(&dummy, 0, sizeof(dummy));
+    dummy.ntiles = h.tiles_per_item;
+    int e;
+    if (h.precise)
+      e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
+    else
+      e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
+    if (e) return hip_fail(e);
+  }
+  return MDBF_OK;
+}
+
+const char* mdbf_strerror(int status) {
+  switch (status) {
+    case MDBF_OK: return "ok";
+    case MDBF_EINVAL: return "invalid argument";
+    case MDBF_EALIGN: return "device pointer not 16-byte aligned";
+    case MDBF_EDTYPE: return "unknown dtype";
+    case MDBF_EWORKSPACE: return "buffer too small";
+    case MDBF_EUNSUPPORTED: return "unsupported request";
+    case MDBF_EHIP: return "HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+const char* mdbf_last_hip_error(void) { return g_hip_err; }
+
+int mdbf_version(void) { return MDBF_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Internal declarations of libmdbf (HIP side only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mdbf.h"
+
+namespace mdbf {
+
+// ---------------------------------------------------------------------------------------
+// Packed sign layout (one bit per entry, bit 1 <=> -1).
+//
+// A sign matrix S (rows x K, contracted along K) is cut into row tiles of 16 rows and column
+// blocks of 128 entries.  One (tile, block) is 64 32-bit words, one per wavefront lane:
+//   lane = kg*16 + r       r  = row inside the tile (0..15), kg = 8-column group (0..3)
+//   local column kl (0..127) of the block:  f = kl/32 (which of the block's four 32-deep
+//   matrix-core steps), kg = (kl%32)/8, e = kl%8, i = e/2, h = e%2
+//   bit index inside the word = 8*(f/2) + 4*(f%2) + i + 16*h
+// so that, with u = w >> 8*(f/2), the word  u & ((1<<(4c+i)) | (1<<(4c+i+16))),  c = f%2,
+// viewed as two fp16 values, holds the entries (e = 2i, 2i+1) as {0 or 2^(4c+i-24)}: the
+// operand of one matrix-core step costs one AND per register and no shift.
+// Blocks of a tile are stored in groups of four, lane-major inside a group (a lane's four
+// words are 16 contiguous bytes); the last 0..3 blocks of a tile are stored block-major.
+// Word offset of (tile t, block q, lane L), KB = blocks per tile, NG = KB/4:
+//   q < 4*NG :  t*KB*64 + (q/4)*256 + L*4 + q%4
+//   else     :  t*KB*64 + NG*256 + (q-4*NG)*64 + L
+// Padding rows/columns hold bit 0.
+// ---------------------------------------------------------------------------------------
+constexpr int kTileRows = 16;
+constexpr int kBlockCols = 128;
+
+__host__ __device__ inline int num_tiles(int rows) { return (rows + kTileRows - 1) / kTileRows; }
+__host__ __device__ inline int num_blocks(int cols) { return (cols + kBlockCols - 1) / kBlockCols; }
+__host__ __device__ inline size_t packed_words(int rows, int cols) {
+  return (size_t)num_tiles(rows) * (size_t)num_blocks(cols) * 64u;
+}
+__host__ __device__ inline size_t word_offset(int tile, int q, int lane, int KB) {
+  const int NG = KB >> 2;
+  size_t base = (size_t)tile * (size_t)KB * 64u;
+  if (q < 4 * NG) return base + (size_t)(q >> 2) * 256u + (size_t)lane * 4u + (size_t)(q & 3);
+  return base + (size_t)NG * 256u + (size_t)(q - 4 * NG) * 64u + (size_t)lane;
+}
+// bit index of local column kl (0..127) inside its lane's word, and the lane's 8-column group
+__host__ __device__ inline int bit_of_local_col(int kl) {
+  const int f = kl >> 5, e = kl & 7, i = e >> 1, h = e & 1;
+  return 8 * (f >> 1) + 4 * (f & 1) + i + 16 * h;
+}
+__host__ __device__ inline int kgroup_of_local_col(int kl) { return (kl & 31) >> 3; }
+
+// ---------------------------------------------------------------------------------------
+// One envelope-scaled binary product ("stage"):
+//   out[b, r] = sum_c Eout[r,c] * ( sum_j S[r,j] * Ein[j,c] * vin[b,j] )      r < rows, b < T
+// Stage 1 of a layer: S=SB, Ein=B, vin=X, Eout=G, out=z (fp32 workspace).
+// Stage 2 of a layer: S=SA, Ein=Q, vin=z, Eout=A, out=Y.
+// ---------------------------------------------------------------------------------------
+struct StageProb {
+  const uint32_t* S;
+  const void* Ein;
+  const void* Eout;
+  const void* vin;
+  void* out;
+  int64_t vin_ld, out_ld;
+  int32_t rows, K, l, T;
+  int32_t KB, ntiles;
+  int32_t env_dt, vin_dt, out_dt;
+  int32_t pad_;
+};
+
+// A unit of work of the stage kernels: row tiles [tile0, tile0+ntiles) of problem `prob`.
+struct WorkItem {
+  int32_t prob, tile0, ntiles, pad_;
+};
+
+// Plan of a batched forward (host and device copies are byte-identical).
+struct PlanHeader {
+  uint32_t magic;
+  int32_t count;              // layers
+  int32_t nitems[2];          // work items of stage 1 / stage 2
+  int32_t tiles_per_item;     // upper bound of WorkItem::ntiles
+  int32_t precise;            // all layers use the fp32 path
+  uint64_t probs_off[2];      // byte offsets of StageProb[count] for stage 1 / 2
+  uint64_t items_off[2];      // byte offsets of WorkItem[nitems[s]]
+  uint64_t total_bytes;
+};
+constexpr uint32_t kPlanMagic = 0x4D444246u;  // "MDBF"
+
+// launchers (defined in the kernel translation units); return hipError_t as int
+int launch_pack(const int8_t* signs, int rows, int cols, int64_t ld, uint32_t* packed, hipStream_t s);
+int launch_unpack(const uint32_t* packed, int rows, int cols, int8_t* signs, int64_t ld, hipStream_t s);
+int launch_stage_precise(const StageProb* probs_dev, const WorkItem* items_dev, int nitems,
+                         const StageProb* single, hipStream_t s);
+int launch_stage_mfma(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
+                      const StageProb* single, hipStream_t s);
+// tiles per work item the matrix-core kernel wants for a problem with `ntiles` row tiles when
+// `total_tiles` tiles are in flight in the same launch
+int mfma_tiles_per_item(long total_tiles);
+
+// dtype helpers (device)
+__device__ inline float load_as_float(const void* p, int64_t idx, int dt) {
+  if (dt == MDBF_F32) return ((const float*)p)[idx];
+  if (dt == MDBF_F16) return (float)((const _Float16*)p)[idx];
+  uint32_t u = ((uint32_t)((const uint16_t*)p)[idx]) << 16;
+  return __builtin_bit_cast(float, u);
+}
+__device__ inline uint16_t float_to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ inline void store_from_float(void* p, int64_t idx, int dt, float v) {
+  if (dt == MDBF_F32) ((float*)p)[idx] = v;
+  else if (dt == MDBF_F16) ((_Float16*)p)[idx] = (_Float16)v;
+  else ((uint16_t*)p)[idx] = float_to_bf16_rne(v);
+}
+__host__ __device__ inline int dtype_size(int dt) { return dt == MDBF_F32 ? 4 : 2; }
+
+}  // namespace mdbf

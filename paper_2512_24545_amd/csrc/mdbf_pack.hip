@@ -1,0 +1,63 @@
+// Sign bit-packing kernels: logical int8 (+-1, row-major)  <->  device tile layout.
+// The layout is described in mdbf_internal.h.  Offline work, not tuned.
+#include "mdbf_internal.h"
+
+namespace mdbf {
+
+// local column (0..127) addressed by bit b of the word of 8-column group kg
+__device__ inline int local_col_of_bit(int b, int kg) {
+  const int h = b >> 4, bb = b & 15;
+  const int f = 2 * (bb >> 3) + ((bb >> 2) & 1), i = bb & 3;
+  return f * 32 + kg * 8 + 2 * i + h;
+}
+
+__global__ void pack_kernel(const int8_t* __restrict__ signs, int rows, int cols, int64_t ld,
+                            uint32_t* __restrict__ packed, int KB, size_t nwords) {
+  size_t widx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (widx >= nwords) return;
+  // enumerate words as (tile, q, lane) and place them through word_offset()
+  const int lane = (int)(widx & 63);
+  const size_t tq = widx >> 6;
+  const int q = (int)(tq % (size_t)KB);
+  const int tile = (int)(tq / (size_t)KB);
+  const int r = lane & 15, kg = lane >> 4;
+  const int row = tile * kTileRows + r;
+  uint32_t w = 0;
+  if (row < rows) {
+    for (int b = 0; b < 32; ++b) {
+      const int col = q * kBlockCols + local_col_of_bit(b, kg);
+      if (col < cols && signs[(int64_t)row * ld + col] < 0) w |= (1u << b);
+    }
+  }
+  packed[word_offset(tile, q, lane, KB)] = w;
+}
+
+__global__ void unpack_kernel(const uint32_t* __restrict__ packed, int rows, int cols,
+                              int8_t* __restrict__ signs, int64_t ld, int KB) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)rows * (size_t)cols) return;
+  const int row = (int)(idx / (size_t)cols), col = (int)(idx % (size_t)cols);
+  const int tile = row / kTileRows, r = row % kTileRows;
+  const int q = col / kBlockCols, kl = col % kBlockCols;
+  const int lane = kgroup_of_local_col(kl) * 16 + r;
+  const uint32_t w = packed[word_offset(tile, q, lane, KB)];
+  signs[(int64_t)row * ld + col] = ((w >> bit_of_local_col(kl)) & 1u) ? (int8_t)-1 : (int8_t)1;
+}
+
+int launch_pack(const int8_t* signs, int rows, int cols, int64_t ld, uint32_t* packed, hipStream_t s) {
+  const size_t nwords = packed_words(rows, cols);
+  const int KB = num_blocks(cols);
+  const unsigned grid = (unsigned)((nwords + 255) / 256);
+  hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, s, signs, rows, cols, ld, packed, KB, nwords);
+  return (int)hipGetLastError();
+}
+
+int launch_unpack(const uint32_t* packed, int rows, int cols, int8_t* signs, int64_t ld, hipStream_t s) {
+  const size_t n = (size_t)rows * (size_t)cols;
+  const int KB = num_blocks(cols);
+  const unsigned grid = (unsigned)((n + 255) / 256);
+  hipLaunchKernelGGL(unpack_kernel, dim3(grid), dim3(256), 0, s, packed, rows, cols, signs, ld, KB);
+  return (int)hipGetLastError();
+}
+
+}  // namespace mdbf

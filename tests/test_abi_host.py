@@ -1,0 +1,136 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/mdbf.h declares,
+its host-only functions agree with the oracle, and every argument error is reported before
+any HIP call (so these run on a host without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import mdbf_oracle as orc
+from paper_2512_24545_amd import binding as mb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mdbf.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(mdbf_[a-z_]+)\s*\(", hdr))
+    assert {"mdbf_pack", "mdbf_unpack", "mdbf_forward", "mdbf_forward_batch", "mdbf_bpw"} <= declared
+    L = mb.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(mb.EXPORTS)
+    assert mb.mdbf_version() == 100
+
+
+def test_bpw_and_rank_match_oracle():
+    for (m, n, k, l) in [(256, 256, 128, 4), (4096, 4096, 2656, 16), (11008, 4096, 4096, 16), (4096, 11008, 4096, 16),
+                         (100, 37, 11, 3)]:
+        assert mb.mdbf_bpw(m, n, k, l) == orc.bits_per_weight(m, n, k, l)
+    assert mb.mdbf_bpw(256, 256, 128, 4) == 1.75
+    assert mb.mdbf_bpw(64, 48, 32, 1, merge_inner=True) == orc.bits_per_weight(64, 48, 32, 1, merge_inner=True)
+    assert mb.mdbf_bpw(64, 48, 32, 2, merge_inner=True) < 0
+    for (m, n, l, bpw) in [(4096, 4096, 16, 1.5), (11008, 4096, 16, 1.5), (4096, 4096, 8, 1.0), (11008, 4096, 8, 1.0),
+                           (4096, 4096, 16, 2.0), (11008, 4096, 16, 2.0), (512, 384, 2, 1.25)]:
+        for mult in (1, 32):
+            assert mb.mdbf_rank_for_budget(m, n, l, bpw, 16, mult) == orc.rank_for_budget(m, n, l, bpw, 16, mult)
+
+
+def test_packed_bytes():
+    # 16-row tiles x 128-column blocks, 64 words each
+    assert mb.mdbf_packed_bytes(16, 128) == 256
+    assert mb.mdbf_packed_bytes(17, 129) == 4 * 256
+    assert mb.mdbf_packed_bytes(4096, 2656) == 256 * 21 * 256
+    out = C.c_size_t(0)
+    assert mb.lib().mdbf_packed_bytes(0, 5, C.byref(out)) == -1
+    assert mb.lib().mdbf_packed_bytes(5, 5, None) == -1
+
+
+FAKE = 0x10000  # a non-null, 16-byte aligned address that is never dereferenced
+
+
+def _call_forward(desc, SA=FAKE, SB=FAKE, env=None, X=FAKE, ldx=None, Y=FAKE, ldy=None, T=1, ws=FAKE, wsb=1 << 30):
+    env = env if env is not None else mb.Env(FAKE, FAKE, FAKE, FAKE)
+    ldx = desc.n if ldx is None else ldx
+    ldy = desc.m if ldy is None else ldy
+    return mb.lib().mdbf_forward(C.byref(desc), SA, SB, C.byref(env), X, ldx, Y, ldy, T, ws, wsb, None)
+
+
+def test_forward_argument_errors_before_any_launch():
+    good = lambda: mb.Desc(64, 48, 32, 4, 0, 0, 2, 0)
+    d = good(); d.l = 17
+    assert _call_forward(d) == -1
+    d = good(); d.l = 0
+    assert _call_forward(d) == -1
+    d = good(); d.m = 0
+    assert _call_forward(d) == -1
+    d = good(); d.x_dtype = 7
+    assert _call_forward(d) == -3
+    d = good(); d.flags = 0x80
+    assert _call_forward(d) == -5
+    d = good()
+    assert _call_forward(d, SA=None) == -1
+    assert _call_forward(d, X=None) == -1
+    assert _call_forward(d, env=mb.Env(FAKE, None, FAKE, FAKE)) == -1
+    assert _call_forward(d, T=0) == -1
+    assert _call_forward(d, ldx=47) == -1
+    assert _call_forward(d, ldy=63) == -1
+    assert _call_forward(d, SB=FAKE + 4) == -2
+    assert _call_forward(d, Y=FAKE + 8) == -2
+    assert _call_forward(d, ws=None) == -1
+    assert _call_forward(d, wsb=16) == -4
+    assert mb.lib().mdbf_forward(None, FAKE, FAKE, None, FAKE, 1, FAKE, 1, 1, FAKE, 0, None) == -1
+
+
+def test_workspace_bytes():
+    d = mb.Desc(4096, 4096, 2656, 16, 0, 0, 0, 0)
+    assert mb.mdbf_workspace_bytes(d, 1) >= 2656 * 4
+    assert mb.mdbf_workspace_bytes(d, 16) >= 16 * 2656 * 4
+    out = C.c_size_t(0)
+    assert mb.lib().mdbf_workspace_bytes(C.byref(d), 0, C.byref(out)) == -1
+
+
+def test_pack_argument_errors():
+    L = mb.lib()
+    assert L.mdbf_pack(None, 4, 4, 4, FAKE, 1 << 20, None) == -1
+    assert L.mdbf_pack(FAKE, 4, 4, 3, FAKE, 1 << 20, None) == -1
+    assert L.mdbf_pack(FAKE, 4, 4, 4, FAKE + 2, 1 << 20, None) == -2
+    assert L.mdbf_pack(FAKE, 4, 4, 4, FAKE, 8, None) == -4
+    assert L.mdbf_unpack(FAKE, 4, 0, FAKE, 4, None) == -1
+
+
+def test_batch_plan_errors_and_sizes():
+    L = mb.lib()
+    arr = (mb.Layer * 2)()
+    for i in range(2):
+        arr[i].desc = mb.Desc(64, 48, 32, 4, 0, 0, 2, 0)
+        arr[i].SA_packed_dev = FAKE
+        arr[i].SB_packed_dev = FAKE
+        arr[i].env = mb.Env(FAKE, FAKE, FAKE, FAKE)
+        arr[i].X_dev = FAKE
+        arr[i].ldx = 48
+        arr[i].Y_dev = FAKE
+        arr[i].ldy = 64
+        arr[i].T = 1
+    pb, wb = C.c_size_t(0), C.c_size_t(0)
+    assert L.mdbf_batch_plan_bytes(2, arr, C.byref(pb), C.byref(wb)) == 0
+    assert pb.value > 0 and wb.value >= 2 * 32 * 4
+    buf = C.create_string_buffer(pb.value)
+    assert L.mdbf_batch_plan_build(2, arr, FAKE, wb.value, buf, pb.value) == 0
+    assert L.mdbf_batch_plan_build(2, arr, FAKE, 8, buf, pb.value) == -4
+    assert L.mdbf_batch_plan_build(2, arr, FAKE, wb.value, buf, 8) == -4
+    arr[1].T = 0
+    assert L.mdbf_batch_plan_bytes(2, arr, C.byref(pb), C.byref(wb)) == -1
+    assert L.mdbf_batch_plan_bytes(0, arr, C.byref(pb), C.byref(wb)) == -1
+    # a plan whose magic is wrong is rejected before any launch
+    bad = C.create_string_buffer(4096)
+    assert L.mdbf_forward_batch(bad, FAKE, 4096, None) == -1
+
+
+def test_strerror():
+    L = mb.lib()
+    assert L.mdbf_strerror(0) == b"ok"
+    assert b"aligned" in L.mdbf_strerror(-2)
+    assert L.mdbf_last_hip_error() == b""

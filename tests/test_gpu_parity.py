@@ -1,0 +1,186 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Gates: sign pack/unpack bit-exact; y within max|Y-Y*|/max|Y*| <= 2e-3 (fp16 staging, fp32
+accumulation); the fp32 ("precise") path within 2e-5; exact-integer inputs bit-for-bit."""
+import numpy as np
+import pytest
+
+from oracle import mdbf_oracle as orc
+from paper_2512_24545_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+TOL_PRECISE = 2e-5
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_2512_24545_amd import binding as mb
+    mb.lib()
+    return torch, mb
+
+
+def _oracle_args(L):
+    return (L["SA"], L["SB"], L["A"], L["Q"], L["G"], L["B"])
+
+
+def _to_dev(torch, X, dtype):
+    t = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[dtype]
+    return torch.from_numpy(np.ascontiguousarray(X)).to("cuda:0").to(t).contiguous()
+
+
+def _run(gpu, L, X, x_dtype, y_dtype="f32", precise=False):
+    torch, mb = gpu
+    dl = mb.DeviceLayer.from_host(L)
+    Xd = _to_dev(torch, X, x_dtype)
+    Y = mb.mdbf_forward(dl, Xd, y_dtype=y_dtype, precise=precise)
+    torch.cuda.synchronize()
+    return Y.float().cpu().numpy().astype(np.float64)
+
+
+# ---------------------------------------------------------------- pack / unpack
+@pytest.mark.parametrize("rows,cols", [(1, 1), (16, 128), (17, 129), (5, 31), (33, 500), (100, 1000),
+                                       (256, 128), (2656, 4096), (4096, 2656)])
+def test_pack_unpack_bit_exact(gpu, rows, cols):
+    torch, mb = gpu
+    rng = np.random.default_rng(rows * 7919 + cols)
+    S = synth.random_signs(rng, rows, cols)
+    Sd = torch.from_numpy(S).to("cuda:0")
+    packed = mb.mdbf_pack(Sd)
+    assert packed.numel() == mb.mdbf_packed_bytes(rows, cols)
+    back = mb.mdbf_unpack(packed, rows, cols).cpu().numpy()
+    np.testing.assert_array_equal(back, S)
+    # the logical bits agree with the oracle's reference packing of the same matrix
+    np.testing.assert_array_equal(orc.pack_ref(back), orc.pack_ref(S))
+    # one bit per entry, padding bits are zero: population count equals the number of -1 entries
+    pc = int(np.unpackbits(packed.cpu().numpy()).sum())
+    assert pc == int((S < 0).sum())
+
+
+def test_pack_zero_is_plus_and_strided_input(gpu):
+    torch, mb = gpu
+    rng = np.random.default_rng(5)
+    big = rng.integers(-3, 4, size=(40, 300)).astype(np.int8)   # includes zeros and |v| > 1
+    view = torch.from_numpy(big).to("cuda:0")[:, 10:210]          # leading dimension 300 > cols 200
+    packed = mb.mdbf_pack(view)
+    back = mb.mdbf_unpack(packed, 40, 200).cpu().numpy()
+    np.testing.assert_array_equal(back, orc.sign_pm1(big[:, 10:210]))
+
+
+# ---------------------------------------------------------------- forward: small and ragged
+SMALL = [
+    # m, n, k, l, T
+    (16, 128, 16, 16, 1),
+    (256, 256, 128, 4, 1),
+    (40, 300, 70, 16, 2),
+    (130, 129, 257, 3, 3),
+    (1, 1, 1, 1, 1),
+    (100, 1030, 200, 8, 1),
+    (530, 2100, 1100, 16, 2),
+    (77, 64, 2656, 2, 1),
+]
+
+
+@pytest.mark.parametrize("m,n,k,l,T", SMALL)
+@pytest.mark.parametrize("precise", [False, True])
+def test_forward_small_shapes(gpu, m, n, k, l, T, precise):
+    L = synth.make_layer(m, n, k, l, seed=m + 3 * n + 5 * k + l, env_dtype="f16", env_kind="unit", signed_env=True)
+    X = synth.make_activations(n, T, seed=99 + m, x_dtype="f16")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, "f16", "f32", precise)
+    err = orc.max_rel_error(got, ref)
+    assert err <= (TOL_PRECISE if precise else TOL), err
+
+
+@pytest.mark.parametrize("env_dtype,x_dtype,y_dtype", [("f32", "f32", "f32"), ("bf16", "bf16", "f32"),
+                                                         ("f16", "f16", "f16"), ("f16", "bf16", "bf16"),
+                                                         ("f32", "f16", "f32")])
+def test_forward_dtypes(gpu, env_dtype, x_dtype, y_dtype):
+    L = synth.make_layer(96, 200, 150, 5, seed=17, env_dtype=env_dtype, env_kind="llama", signed_env=True)
+    X = synth.make_activations(200, 2, seed=18, x_dtype=x_dtype)
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, x_dtype, y_dtype)
+    # a 16-bit output adds its own rounding: half an ulp of the largest element
+    slack = {"f32": 0.0, "f16": 2.0 ** -11, "bf16": 2.0 ** -8}[y_dtype]
+    assert orc.max_rel_error(got, ref) <= TOL + slack
+
+
+def test_toy_config(gpu):
+    """256x256, k=128, l=4, fp32 envelopes and activations."""
+    L, X = synth.config_toy()
+    ref = orc.forward_dense(*_oracle_args(L), X)
+    np.testing.assert_allclose(orc.forward_factored(*_oracle_args(L), X), ref, rtol=1e-10, atol=1e-9)
+    for precise, tol in ((False, TOL), (True, TOL_PRECISE)):
+        got = _run(gpu, L, X, "f32", "f32", precise)
+        assert orc.max_rel_error(got, ref) <= tol
+
+
+# ---------------------------------------------------------------- exact-integer inputs: zero tolerance
+@pytest.mark.parametrize("m,n,k,l", [(64, 256, 96, 4), (530, 2100, 1100, 16), (4096, 4096, 2656, 4)])
+def test_exact_integer_inputs_bit_for_bit(gpu, m, n, k, l):
+    """All-ones envelopes and x in {-1,0,1}: every intermediate is an integer that fp16 staging and
+    fp32 accumulation represent exactly, so the result must equal the oracle in any summation order."""
+    L = synth.make_layer(m, n, k, l, seed=31 + m, env_dtype="f16", env_kind="ones")
+    X = synth.make_activations(n, 1, seed=32, x_dtype="f16", kind="ternary")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    assert np.max(np.abs(ref)) < 2 ** 24
+    got = _run(gpu, L, X, "f16", "f32")
+    np.testing.assert_array_equal(got, ref)
+
+
+# ---------------------------------------------------------------- LLaMA-7B shaped layers
+def test_attention_projection_decode(gpu):
+    """4096x4096, k=2656, l=16, one fp16 token (about 1.5 bits per weight)."""
+    L, X = synth.config_attn_decode()
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, "f16", "f32")
+    assert orc.max_rel_error(got, ref) <= TOL
+    got16 = _run(gpu, L, X, "f16", "f16")
+    assert orc.max_rel_error(got16, ref) <= TOL + 2.0 ** -11
+
+
+@pytest.mark.parametrize("which", ["gate", "down"])
+@pytest.mark.parametrize("T", [1, 16])
+def test_mlp_projections_decode(gpu, which, T):
+    L, X = synth.config_mlp_decode(which, T=T)
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, "f16", "f32")
+    assert orc.max_rel_error(got, ref) <= TOL
+
+
+def test_determinism(gpu):
+    torch, mb = gpu
+    L, X = synth.config_attn_decode(seed=7, T=2)
+    dl = mb.DeviceLayer.from_host(L)
+    Xd = _to_dev(torch, X, "f16")
+    Y1 = mb.mdbf_forward(dl, Xd).clone()
+    Y2 = mb.mdbf_forward(dl, Xd)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
+
+
+# ---------------------------------------------------------------- many layers in one launch pair
+def test_batch_matches_single_calls(gpu):
+    torch, mb = gpu
+    specs = [(256, 256, 128, 4), (530, 2100, 1100, 16), (100, 1030, 200, 8), (4096, 4096, 2656, 16)]
+    layers, Xs, Ys, singles = [], [], [], []
+    for i, (m, n, k, l) in enumerate(specs):
+        L = synth.make_layer(m, n, k, l, seed=400 + i, env_dtype="f16", env_kind="llama")
+        X = synth.make_activations(n, 1 + (i % 2), seed=500 + i, x_dtype="f16")
+        dl = mb.DeviceLayer.from_host(L)
+        Xd = _to_dev(torch, X, "f16")
+        layers.append(dl)
+        Xs.append(Xd)
+        Ys.append(torch.zeros((Xd.shape[0], m), dtype=torch.float32, device="cuda:0"))
+        singles.append(mb.mdbf_forward(dl, Xd))
+        ref = orc.forward_factored(*_oracle_args(L), X)
+        assert orc.max_rel_error(singles[-1].cpu().numpy(), ref) <= TOL
+    plan = mb.BatchPlan(layers, Xs, Ys)
+    plan.run()
+    torch.cuda.synchronize()
+    for Yb, Ys1 in zip(Ys, singles):
+        assert torch.equal(Yb, Ys1)
