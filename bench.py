@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the MDBF forward product on one MI355X.
+
+Workload (N=1): the LLaMA-7B attention projection as a decode GEMV -- m=n=4096, k=2656, l=16,
+one fp16 token, about 1.5 bits/weight.  One "step" is one pass of the whole hot path (pack is
+offline; scale-in, binary product 1, envelope accumulate + re-scale, binary product 2, envelope
+accumulate) over one batch of `copies` INDEPENDENT layers of that shape, each with its own
+signs, envelopes and activation vector, resident in HBM.  The batch exceeds 1 GB, several times
+the 256 MB last-level cache, so every step streams its weights from HBM.  The batch is issued
+through mdbf_forward_batch (two kernel launches per step).  Also reported, never as `value`:
+the same layers issued as one mdbf_forward call each from a HIP graph, one layer re-run hot
+in cache, and the latency of a single call.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+M, N, K, L = 4096, 4096, 2656, 16
+
+
+def algorithmic_bytes(m, n, k, l, T=1, ebytes=2, xbytes=2, ybytes=2):
+    """Bytes one forward call must move: packed signs + envelope factors + x + y."""
+    signs = (m + n) * k // 8
+    env = ebytes * l * (m + n + 2 * k)
+    return signs + env + T * (xbytes * n + ybytes * m)
+
+
+def make_device_layers(torch, mb, copies, seed):
+    """`copies` independent layers generated on the device from one seed: i.i.d. sign bits,
+    envelopes |N(0,1)|*0.02 + 1e-3 (fp16), activations N(0,1) (fp16)."""
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    layers, Xs, Ys = [], [], []
+    nb_sa = mb.mdbf_packed_bytes(M, K)
+    nb_sb = mb.mdbf_packed_bytes(K, N)
+
+    def env(rows):
+        return (torch.randn((rows, L), generator=g, device="cuda:0").abs() * 0.02 + 1e-3).half()
+
+    for _ in range(copies):
+        sa = torch.randint(-2 ** 31, 2 ** 31 - 1, (nb_sa // 4,), dtype=torch.int32, generator=g, device="cuda:0")
+        sb = torch.randint(-2 ** 31, 2 ** 31 - 1, (nb_sb // 4,), dtype=torch.int32, generator=g, device="cuda:0")
+        layers.append(mb.DeviceLayer(M, N, K, L, sa.view(torch.uint8), sb.view(torch.uint8),
+                                     env(M), env(K), env(K), env(N)))
+        Xs.append(torch.randn((1, N), generator=g, device="cuda:0").half())
+        Ys.append(torch.zeros((1, M), dtype=torch.float16, device="cuda:0"))
+    return layers, Xs, Ys
+
+
+def oracle_check(torch, mb, layer, X, Y):
+    """Download one layer (logical signs through mdbf_unpack) and compare with the CPU oracle."""
+    from oracle import mdbf_oracle as orc
+    SA = mb.mdbf_unpack(layer.SA_packed, M, K).cpu().numpy()
+    SB = mb.mdbf_unpack(layer.SB_packed, K, N).cpu().numpy()
+    args = (SA, SB, layer.A.float().cpu().numpy(), layer.Q.float().cpu().numpy(),
+            layer.G.float().cpu().numpy(), layer.B.float().cpu().numpy())
+    ref = orc.forward_factored(*args, X.float().cpu().numpy())
+    return orc.max_rel_error(Y.float().cpu().numpy(), ref), args
+
+
+def cpu_baseline(args, X, budget_s=12.0):
+    """The oracle's factored forward, as it stands, on the host cores."""
+    from oracle import mdbf_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Xh = X.float().cpu().numpy()
+    orc.forward_factored(*args, Xh)
+    t0 = time.perf_counter()
+    calls = 0
+    while True:
+        orc.forward_factored(*args, Xh)
+        calls += 1
+        if time.perf_counter() - t0 > budget_s or calls >= 200:
+            break
+    dt = (time.perf_counter() - t0) / calls
+    return {"value": algorithmic_bytes(M, N, K, L) / dt / 1e9, "unit": "GB/s", "cores": int(cores),
+            "kind": "oracle", "ms_per_call": dt * 1e3,
+            "sample": "%d forward calls of the numpy fp64 oracle (factored order) on one 4096x4096 k=2656 l=16 layer"
+                      % calls}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--copies", type=int, default=336, help="independent layers per step (336 x 3.17 MB > 1 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the graph / hot / latency side measurements")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (--gpus 1); the forward product of one layer "
+              "is a single-GPU kernel and no multi-GPU path exists", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_24545_amd import binding as mb
+    mb.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    layers, Xs, Ys = make_device_layers(torch, mb, a.copies, seed=2)
+    plan = mb.BatchPlan(layers, Xs, Ys)
+    bytes_call = algorithmic_bytes(M, N, K, L)
+    bytes_step = bytes_call * a.copies
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- the timed region: K steps of the batched path
+    for _ in range(a.warmup):
+        plan.run()
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(a.steps):
+        plan.run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_total = e0.elapsed_time(e1)
+    ms_step = ms_total / a.steps
+    gbs = bytes_step / ms_step / 1e6
+
+    err, host_args = oracle_check(torch, mb, layers[0], Xs[0], Ys[0])
+    err_last, _ = oracle_check(torch, mb, layers[-1], Xs[-1], Ys[-1])
+
+    # ---- roofline of the dominant kernel (the stage kernel; two launches per step)
+    launches = 2 * a.steps
+    avg_launch_ms = ms_total / launches
+    roof = {"bound": "hbm", "kernel": "stage_mfma_kernel", "achieved": (bytes_step / 2) / avg_launch_ms / 1e6,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None,
+            "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_step / 2}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+
+    extras = {}
+    if not a.no_extras:
+        # (1) one mdbf_forward call per layer, replayed from a HIP graph
+        ws = [torch.empty(mb.mdbf_workspace_bytes(l.desc("f16", "f16"), 1), dtype=torch.uint8, device="cuda:0")
+              for l in layers]
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            for i in range(min(4, a.copies)):
+                mb.mdbf_forward(layers[i], Xs[i], y_dtype="f16", Y=Ys[i], workspace=ws[i])
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            for i in range(a.copies):
+                mb.mdbf_forward(layers[i], Xs[i], y_dtype="f16", Y=Ys[i], workspace=ws[i])
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        reps = 5
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us_call = e0.elapsed_time(e1) * 1e3 / (reps * a.copies)
+        extras["per_call_graph"] = {"us_per_call": us_call, "GB/s": bytes_call / us_call / 1e3}
+        # (2) the same layer again and again (cache resident) through the batched entry point
+        hot = mb.BatchPlan([layers[0]] * 64, [Xs[0]] * 64, [Ys[0]] * 64)
+        hot.run()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            hot.run()
+        e1.record()
+        torch.cuda.synchronize()
+        extras["hot_in_cache"] = {"GB/s": 64 * bytes_call * 10 / e0.elapsed_time(e1) / 1e6}
+        # (3) latency of one isolated call (two launches), stream-ordered
+        e0.record()
+        for _ in range(200):
+            mb.mdbf_forward(layers[1], Xs[1], y_dtype="f16", Y=Ys[1], workspace=ws[1])
+        e1.record()
+        torch.cuda.synchronize()
+        extras["single_call_stream"] = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 200}
+
+    out = {
+        "metric": "MDBF decode GEMV HBM GB/s (% peak) + prefill TFLOP/s, LLaMA-7B shapes",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "attn_decode 4096x4096 k=2656 l=16 T=1 (1.503 bpw), %d independent layers per step "
+                               "via mdbf_forward_batch" % a.copies,
+                   "copies": a.copies, "algorithmic_bytes_per_call": bytes_call,
+                   "bytes_per_step": bytes_step},
+        "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "us_per_layer": ms_step * 1e3 / a.copies,
+        "max_rel_err_vs_oracle": max(err, err_last),
+        "roofline": roof,
+    }
+    out.update(extras)
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(host_args, Xs[0])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
