@@ -22,7 +22,7 @@ int hip_fail(int e) {
 bool valid_dtype(int d) { return d == MDBF_F16 || d == MDBF_BF16 || d == MDBF_F32; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-int kpad_of(int k) { return (k + 3) & ~3; }  // z rows are 16-byte aligned
+int kpad_of(int k) { return (k + 7) & ~7; }  // z rows stay 32-byte aligned
 
 int check_desc(const mdbf_desc_t* d) {
   if (!d) return MDBF_EINVAL;
@@ -161,8 +161,10 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
     int e;
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
-    else
+    else if (stage_is_fast(sp[i]))
       e = launch_stage_mfma(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], s);
+    else
+      e = launch_stage_generic(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], s);
     if (e) return hip_fail(e);
   }
   return MDBF_OK;
@@ -241,6 +243,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   WorkItem* items[2] = {(WorkItem*)(base + h.items_off[0]), (WorkItem*)(base + h.items_off[1])};
   size_t zoff = 0;
   int ni[2] = {0, 0};
+  int fast[2] = {1, 1};
   const int tpi = h.tiles_per_item;
   for (int i = 0; i < count; ++i) {
     const mdbf_layer_t* L = &layers[i];
@@ -250,6 +253,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
     zoff += z_bytes(&L->desc, L->T);
     for (int s = 0; s < 2; ++s) {
       probs[s][i] = sp[s];
+      if (!stage_is_fast(sp[s])) fast[s] = 0;
       for (int t0 = 0; t0 < sp[s].ntiles; t0 += tpi) {
         WorkItem w;
         w.prob = i;
@@ -260,6 +264,9 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
       }
     }
   }
+  h.fast[0] = fast[0];
+  h.fast[1] = fast[1];
+  memcpy(base, &h, sizeof(h));
   return MDBF_OK;
 }
 
@@ -281,8 +288,10 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
     int e;
     if (h.precise)
       e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
-    else
+    else if (h.fast[st])
       e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
+    else
+      e = launch_stage_generic(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
     if (e) return hip_fail(e);
   }
   return MDBF_OK;

@@ -77,6 +77,8 @@ struct PlanHeader {
   int32_t nitems[2];          // work items of stage 1 / stage 2
   int32_t tiles_per_item;     // upper bound of WorkItem::ntiles
   int32_t precise;            // all layers use the fp32 path
+  int32_t fast[2];            // every problem of the stage qualifies for the fast matrix-core variant
+  int32_t pad_[2];
   uint64_t probs_off[2];      // byte offsets of StageProb[count] for stage 1 / 2
   uint64_t items_off[2];      // byte offsets of WorkItem[nitems[s]]
   uint64_t total_bytes;
@@ -90,6 +92,11 @@ int launch_stage_precise(const StageProb* probs_dev, const WorkItem* items_dev, 
                          const StageProb* single, hipStream_t s);
 int launch_stage_mfma(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
                       const StageProb* single, hipStream_t s);
+int launch_stage_generic(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
+                         const StageProb* single, hipStream_t s);
+// true if the fast matrix-core variant can run the problem (l == 16, fp16 envelopes, K % 8 == 0,
+// 16-byte aligned activation rows); otherwise the general variant is used
+bool stage_is_fast(const StageProb& p);
 // tiles per work item the matrix-core kernel wants for a problem with `ntiles` row tiles when
 // `total_tiles` tiles are in flight in the same launch
 int mfma_tiles_per_item(long total_tiles);

@@ -1,4 +1,5 @@
-// Matrix-core evaluation of one envelope-scaled binary product on gfx950.
+// Matrix-core evaluation of one envelope-scaled binary product on gfx950: the FAST variant
+// (l == 16, fp16 envelopes, K a multiple of 8, 16-byte aligned activation rows).
 //
 //   out[r] = sum_c Eout[r,c] * P[r,c],     P[r,c] = sum_j S[r,j] * xs[j,c],   xs[j,c] = fp16(Ein[j,c] * vin[j])
 //
@@ -8,7 +9,9 @@
 // Work decomposition: a workgroup of four wavefronts owns up to 4*R row tiles (16 rows each) of
 // one problem and the whole contraction; wave w owns tiles w, w+4, ...  The scaled activations xs
 // are staged chunk by chunk (1024 columns) in LDS in the order the MFMA B operand wants them and
-// shared by all tiles of the workgroup; sign words stream from HBM with 128-bit loads.
+// shared by all tiles of the workgroup; sign words stream from HBM with 128-bit loads, one group
+// (512 columns) ahead of their use; the envelope rows of the next chunk are in flight while the
+// current chunk is contracted.
 //
 // Sign expansion without shifts: with bit t=1 meaning -1,  S = 1 - 2t, hence
 //      P[r,c] = colsum[c] - 2 * sum_j t[r,j] xs[j,c].
@@ -17,21 +20,30 @@
 // staged activation of the entry at position p = 4c+i carries the factor 2^-i, so every product of
 // class c (positions 4c..4c+3) is scaled by 2^(4c-24) exactly, and each class has its own fp32
 // accumulator.  Bits 8..15 of each half word are brought down with one shift per word.
+// colsum comes from the same MFMAs applied to a virtual row whose bits are all 1, so that it sees
+// exactly the staged (rounded) values; the four waves share that work block by block.
 #include "mdbf_internal.h"
 
 namespace mdbf {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+#define MDBF_GLOBAL __attribute__((address_space(1)))
+typedef const MDBF_GLOBAL u32x4* g_u32x4_ptr;
+typedef const MDBF_GLOBAL uint32_t* g_u32_ptr;
+typedef const MDBF_GLOBAL floatx4* g_f32x4_ptr;
+typedef const MDBF_GLOBAL _Float16* g_f16_ptr;
+typedef const MDBF_GLOBAL uint16_t* g_u16_ptr;
+typedef const MDBF_GLOBAL float* g_f32_ptr;
+
 constexpr int CB = 8;                      // 128-column blocks per LDS chunk
 constexpr int kChunkVecs = CB * 4 * 64;    // 16-byte vectors per chunk buffer (32 KB)
-constexpr int kSmemBytes = 2 * kChunkVecs * 16 + 4 * 16 * 4;
+constexpr int kFastSmemBytes = 2 * kChunkVecs * 16 + 4 * 16 * 4;
 
-__device__ inline half8 expand(uint32_t src, int c) {
-  // class c: bit positions 4c..4c+3 and 16 above
+__device__ __forceinline__ half8 expand(uint32_t src, int c) {
+  // class c: bit positions 4c..4c+3 and the same 16 above
   const uint32_t m0 = 0x00010001u << (4 * c);
   u32x4 a;
   a.x = src & m0;
@@ -41,178 +53,238 @@ __device__ inline half8 expand(uint32_t src, int c) {
   return __builtin_bit_cast(half8, a);
 }
 
-template <int R>
-__global__ __launch_bounds__(256) void stage_mfma_kernel(const StageProb* __restrict__ probs,
-                                                         const WorkItem* __restrict__ items,
-                                                         StageProb single, int tiles_per_item) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u32x4* buf = reinterpret_cast<u32x4*>(smem);
-  float* red = reinterpret_cast<float*>(smem + 2 * kChunkVecs * 16);
+// {fp16(lo16(e0) * x0), fp16(lo16(e1) * x1)} with one rounding each (mixed-precision fma)
+__device__ __forceinline__ uint32_t mix_pair_lo(uint32_t e0, uint32_t e1, float x0, float x1) {
+  uint32_t out;
+  asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(out) : "v"(e0), "v"(x0));
+  asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "+v"(out) : "v"(e1), "v"(x1));
+  return out;
+}
+// the same for the upper halves of e0, e1
+__device__ __forceinline__ uint32_t mix_pair_hi(uint32_t e0, uint32_t e1, float x0, float x1) {
+  uint32_t out;
+  asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(out) : "v"(e0), "v"(x0));
+  asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(out) : "v"(e1), "v"(x1));
+  return out;
+}
 
-  const StageProb* pp;
-  int tile0, ntl;
-  if (probs) {
-    const WorkItem it = items[blockIdx.x];
-    pp = &probs[it.prob];
-    tile0 = it.tile0;
-    ntl = it.ntiles;
-  } else {
-    pp = &single;
-    tile0 = blockIdx.x * tiles_per_item;
-    ntl = min(tiles_per_item, single.ntiles - tile0);
-  }
-  const StageProb p = *pp;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // tiles of this wave: tile0 + wave + 4*jj for jj < nt
-  int nt = (ntl - wave + 3) / 4;
-  nt = nt < 0 ? 0 : (nt > R ? R : nt);
-  const int KB = p.KB, NG = KB >> 2;
-  const int ngroups = (KB + 3) >> 2;
-  const int nchunks = (KB + CB - 1) / CB;
+// sum over the 16 lanes of a DPP row (result valid in every lane of the row)
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+  return v;
+}
 
-  const uint32_t* sbase[R];
+struct StageRegs {
+  u32x4 e[8];   // 8 envelope rows of one column octet, 8 fp16 modes each
+  float x[8];   // the octet's 8 activations, already multiplied by 2^-(e/2)
+};
+
+// Thread (oo = tid/2, ch = tid%2) stages the octet of columns `kcol..kcol+7` for modes 8ch..8ch+7.
+__device__ __forceinline__ void stage_load(g_u32x4_ptr ein_thr, const void* vin_row, int vin_dt, int kcol, int K,
+                                           StageRegs& sr) {
+  if (kcol < K) {
+    g_u32x4_ptr ep = ein_thr + (size_t)kcol * 2;
 #pragma unroll
-  for (int r = 0; r < R; ++r) sbase[r] = p.S + (size_t)(tile0 + wave + 4 * r) * (size_t)KB * 64u;
-
-  auto load_group = [&](int g, u32x4 (&w)[R]) {
-    if (g < NG) {
+    for (int e = 0; e < 8; ++e) sr.e[e] = ep[2 * e];
+    if (vin_dt == MDBF_F32) {
+      g_f32x4_ptr xp = (g_f32x4_ptr)((g_f32_ptr)vin_row + kcol);
+      const floatx4 x0 = xp[0], x1 = xp[1];
+      sr.x[0] = x0.x; sr.x[1] = x0.y; sr.x[2] = x0.z * 0.5f; sr.x[3] = x0.w * 0.5f;
+      sr.x[4] = x1.x * 0.25f; sr.x[5] = x1.y * 0.25f; sr.x[6] = x1.z * 0.125f; sr.x[7] = x1.w * 0.125f;
+    } else if (vin_dt == MDBF_F16) {
+      const u32x4 xb = *(g_u32x4_ptr)((g_f16_ptr)vin_row + kcol);
+      const half8 xh = __builtin_bit_cast(half8, xb);
 #pragma unroll
-      for (int r = 0; r < R; ++r)
-        if (r < nt) w[r] = *reinterpret_cast<const u32x4*>(sbase[r] + (size_t)g * 256u + (size_t)lane * 4u);
+      for (int e = 0; e < 8; ++e) sr.x[e] = (float)xh[e] * (1.0f / (float)(1 << (e >> 1)));
     } else {
-      const int nb = KB - 4 * NG;  // 1..3 tail blocks, stored block-major
+      const u32x4 xb = *(g_u32x4_ptr)((g_u16_ptr)vin_row + kcol);
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        u32x4 t = {0u, 0u, 0u, 0u};
-        if (r < nt) {
-          const uint32_t* tb = sbase[r] + (size_t)NG * 256u + lane;
-          t.x = tb[0];
-          if (nb > 1) t.y = tb[64];
-          if (nb > 2) t.z = tb[128];
-        }
-        w[r] = t;
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t wd = xb[e >> 1];
+        const uint32_t bits = (e & 1) ? (wd & 0xFFFF0000u) : (wd << 16);
+        sr.x[e] = __builtin_bit_cast(float, bits) * (1.0f / (float)(1 << (e >> 1)));
       }
     }
-  };
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sr.e[e] = u32x4{0u, 0u, 0u, 0u};
+      sr.x[e] = 0.f;
+    }
+  }
+}
+
+// dst: the thread's 8 consecutive 16-byte slots (modes 8ch..8ch+7 of its octet); slot cc is stored at
+// cc ^ sw so that the 64 lanes of one store instruction spread over all LDS banks.
+__device__ __forceinline__ void stage_store(const StageRegs& sr, u32x4* dst, int sw) {
+#pragma unroll
+  for (int cc = 0; cc < 8; ++cc) {
+    u32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u32x4 r0 = sr.e[2 * i], r1 = sr.e[2 * i + 1];
+      const uint32_t a0 = r0[cc >> 1], a1 = r1[cc >> 1];
+      const uint32_t pr = (cc & 1) ? mix_pair_hi(a0, a1, sr.x[2 * i], sr.x[2 * i + 1])
+                                   : mix_pair_lo(a0, a1, sr.x[2 * i], sr.x[2 * i + 1]);
+      v[i] = pr;
+    }
+    dst[cc ^ sw] = v;
+  }
+}
+
+template <int R, bool FULL>
+__device__ __forceinline__ void contract_block(const u32x4* __restrict__ blk_even, const u32x4* __restrict__ blk_odd,
+                                               bool do_virtual, const uint32_t (&word)[R], int nt,
+                                               floatx4 (&acc)[R][2], floatx4 (&accv)[2]) {
+  half8 bop[4];
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+    const u32x4 t = (f & 1) ? blk_odd[f * 64] : blk_even[f * 64];
+    bop[f] = __builtin_bit_cast(half8, t);
+  }
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (FULL || r < nt) {
+        const uint32_t src = (f < 2) ? word[r] : (word[r] >> 8);
+        acc[r][f & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(expand(src, f & 1), bop[f], acc[r][f & 1], 0, 0, 0);
+      }
+    }
+  }
+  if (do_virtual) {
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+      accv[f & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(expand(0xFFFFFFFFu, f & 1), bop[f], accv[f & 1], 0, 0, 0);
+  }
+}
+
+template <int R, bool FULL>
+__device__ __forceinline__ void run_item(const StageProb& p, const int tile0, const int ntl, u32x4* buf, float* red) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int nt = (ntl - wave + 3) / 4;   // tiles of this wave: tile0 + wave + 4*jj, jj < nt
+  nt = nt < 0 ? 0 : (nt > R ? R : nt);
+  const int KB = p.KB, NG = KB >> 2, TB = KB & 3;
+  const int nchunks = (KB + CB - 1) / CB;
+
+  // sign words: 16-byte vectors, this lane's slot of its wave's first tile
+  const int tstride = 4 * KB * 16;  // vectors between consecutive tiles of one wave
+  g_u32x4_ptr sp = (g_u32x4_ptr)p.S + (size_t)(tile0 + wave) * (size_t)(KB * 16) + lane;
+  g_u32_ptr stail = (g_u32_ptr)p.S + (size_t)(tile0 + wave) * (size_t)(KB * 64) + (size_t)NG * 256 + lane;
+
+  // staging role of this thread
+  const int ch = tid & 1, oo = tid >> 1;
+  const int st_q = oo >> 4, st_f = (oo & 15) >> 2, st_kg = oo & 3;
+  const int st_col = st_q * kBlockCols + st_f * 32 + st_kg * 8;            // column inside a chunk
+  const int st_vec = (st_q * 4 + st_f) * 64 + st_kg * 16 + ch * 8;         // first of its 8 LDS slots
+  const int st_sw = (st_kg + 4 * (st_f & 1)) & 7;
+  g_u32x4_ptr ein_thr = (g_u32x4_ptr)p.Ein + ch;
+
+  // B-operand read slots of this lane (same swizzle as the stores)
+  const int kg = lane >> 4, n = lane & 15;
+  const int rd_even = kg * 16 + ((n & 8) | ((n & 7) ^ (kg & 7)));
+  const int rd_odd = kg * 16 + ((n & 8) | ((n & 7) ^ ((kg + 4) & 7)));
 
   for (int b = 0; b < p.T; ++b) {
+    const void* vin_row = (const char*)p.vin + (size_t)b * (size_t)p.vin_ld * (size_t)dtype_size(p.vin_dt);
     floatx4 acc[R][2];
+    floatx4 accv[2];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       acc[r][0] = floatx4{0.f, 0.f, 0.f, 0.f};
       acc[r][1] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    float cs[8];
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc) cs[cc] = 0.f;
+    accv[0] = floatx4{0.f, 0.f, 0.f, 0.f};
+    accv[1] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 wnext[R];
+    u32x4 wn[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) wnext[r] = u32x4{0u, 0u, 0u, 0u};
-    load_group(0, wnext);
+    for (int r = 0; r < R; ++r) wn[r] = u32x4{0u, 0u, 0u, 0u};
+    if (NG > 0) {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if (FULL || r < nt) wn[r] = sp[r * tstride];
+    }
 
+    StageRegs sr;
+    stage_load(ein_thr, vin_row, p.vin_dt, st_col, p.K, sr);
+    stage_store(sr, buf + st_vec, st_sw);
+    __syncthreads();
+
+#pragma unroll 1
     for (int c = 0; c < nchunks; ++c) {
-      u32x4* bufc = buf + (c & 1) * kChunkVecs;
-      // ---- stage xs for columns [c*1024, c*1024+1024) into LDS, B-operand order --------------
-      for (int oo = tid >> 1; oo < CB * 16; oo += 128) {
-        const int ch = tid & 1;
-        const int qloc = oo >> 4, f = (oo & 15) >> 2, kg = oo & 3;
-        const int kbase = (c * CB + qloc) * kBlockCols + f * 32 + kg * 8;
-        _Float16 h[8][8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int k = kbase + e;
-          const float beta = (e >> 1) == 0 ? 1.f : (e >> 1) == 1 ? 0.5f : (e >> 1) == 2 ? 0.25f : 0.125f;
-          const float rbeta = (float)(1 << (e >> 1));
-          float vk = 0.f;
-          if (k < p.K) vk = load_as_float(p.vin, (int64_t)b * p.vin_ld + k, p.vin_dt);
-#pragma unroll
-          for (int cc = 0; cc < 8; ++cc) {
-            const int s = ch * 8 + cc;
-            float ev = 0.f;
-            if (k < p.K && s < p.l) ev = load_as_float(p.Ein, (int64_t)k * p.l + s, p.env_dt);
-            const _Float16 hv = (_Float16)((ev * vk) * beta);
-            h[e][cc] = hv;
-            cs[cc] += (float)hv * rbeta;
-          }
-        }
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc) {
-          half8 v;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = h[e][cc];
-          bufc[(qloc * 4 + f) * 64 + kg * 16 + ch * 8 + cc] = __builtin_bit_cast(u32x4, v);
-        }
-      }
-      __syncthreads();
-      // ---- contract this chunk ---------------------------------------------------------------
+      const u32x4* bufc = buf + (c & 1) * kChunkVecs;
+      const bool more = (c + 1 < nchunks);
+      if (more) stage_load(ein_thr, vin_row, p.vin_dt, (c + 1) * (CB * kBlockCols) + st_col, p.K, sr);
+      // ---- full groups of this chunk ---------------------------------------------------------
 #pragma unroll
       for (int gi = 0; gi < CB / 4; ++gi) {
         const int g = c * (CB / 4) + gi;
-        if (g < ngroups) {
+        if (g < NG) {
           u32x4 w[R];
 #pragma unroll
-          for (int r = 0; r < R; ++r) w[r] = wnext[r];
-          if (g + 1 < ngroups) load_group(g + 1, wnext);
-          const int nb = min(4, KB - 4 * g);
+          for (int r = 0; r < R; ++r) w[r] = wn[r];
+          if (g + 1 < NG) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+              if (FULL || r < nt) wn[r] = sp[(g + 1) * 64 + r * tstride];
+          }
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            if (j < nb) {
+            uint32_t word[R];
 #pragma unroll
-              for (int f = 0; f < 4; ++f) {
-                const half8 bop = __builtin_bit_cast(half8, bufc[((gi * 4 + j) * 4 + f) * 64 + lane]);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                  if (r < nt) {
-                    const uint32_t word = w[r][j];
-                    const uint32_t src = (f < 2) ? word : (word >> 8);
-                    acc[r][f & 1] =
-                        __builtin_amdgcn_mfma_f32_16x16x32_f16(expand(src, f & 1), bop, acc[r][f & 1], 0, 0, 0);
-                  }
-                }
-              }
+            for (int r = 0; r < R; ++r) {
+              const u32x4 t = w[r];
+              word[r] = t[j];
             }
+            const u32x4* blk = bufc + (gi * 4 + j) * 256;
+            contract_block<R, FULL>(blk + rd_even, blk + rd_odd, wave == j, word, nt, acc, accv);
           }
         }
       }
+      // ---- the 1..3 tail blocks (stored block-major) live in the last chunk ---------------------
+      if (TB != 0 && c == nchunks - 1) {
+        for (int tb = 0; tb < TB; ++tb) {
+          const int q = 4 * NG + tb;
+          uint32_t word[R];
+#pragma unroll
+          for (int r = 0; r < R; ++r) {
+            word[r] = 0u;
+            if (FULL || r < nt) word[r] = stail[(size_t)r * (size_t)(4 * KB * 64) + tb * 64];
+          }
+          const u32x4* blk = bufc + (q - c * CB) * 256;
+          contract_block<R, FULL>(blk + rd_even, blk + rd_odd, wave == (q & 3), word, nt, acc, accv);
+        }
+      }
+      if (more) stage_store(sr, buf + ((c + 1) & 1) * kChunkVecs + st_vec, st_sw);
+      __syncthreads();
     }
 
-    // ---- column sums of xs: reduce over the threads that staged the same column half ----------
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc) {
-      float v = cs[cc];
-      v += __shfl_xor(v, 2);
-      v += __shfl_xor(v, 4);
-      v += __shfl_xor(v, 8);
-      v += __shfl_xor(v, 16);
-      v += __shfl_xor(v, 32);
-      cs[cc] = v;
-    }
-    if (lane < 2) {
-#pragma unroll
-      for (int cc = 0; cc < 8; ++cc) red[wave * 16 + lane * 8 + cc] = cs[cc];
-    }
+    // ---- column sums of xs from the virtual all-ones row (all its output rows are equal) --------
+    if (lane < 16) red[wave * 16 + lane] = accv[0][0] * 16777216.f + accv[1][0] * 1048576.f;  // 2^24, 2^20
     __syncthreads();
-    const int s = lane & 15;
-    const float colsum = (red[s] + red[16 + s]) + (red[32 + s] + red[48 + s]);
+    const float colsum = (red[n] + red[16 + n]) + (red[32 + n] + red[48 + n]);
 
     // ---- fix-up, envelope accumulate, store ----------------------------------------------------
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      if (r < nt) {
-        const int rowb = (tile0 + wave + 4 * r) * kTileRows + 4 * (lane >> 4);
+      if (FULL || r < nt) {
+        const int rowb = (tile0 + wave + 4 * r) * kTileRows + 4 * kg;
+        float ev[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = rowb + i;
+          ev[i] = (row < p.rows) ? (float)((g_f16_ptr)p.Eout)[(size_t)row * 16 + n] : 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int row = rowb + i;
           const float P = colsum - acc[r][0][i] * 33554432.f - acc[r][1][i] * 2097152.f;  // 2^25, 2^21
-          float ev = 0.f;
-          if (row < p.rows && s < p.l) ev = load_as_float(p.Eout, (int64_t)row * p.l + s, p.env_dt);
-          float v = ev * P;
-          v += __shfl_xor(v, 1);
-          v += __shfl_xor(v, 2);
-          v += __shfl_xor(v, 4);
-          v += __shfl_xor(v, 8);
-          if (s == 0 && row < p.rows) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, v);
+          const float v = row16_sum(ev[i] * P);
+          if (n == 0 && row < p.rows) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, v);
         }
       }
     }
@@ -221,25 +293,63 @@ __global__ __launch_bounds__(256) void stage_mfma_kernel(const StageProb* __rest
 }
 
 template <int R>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void stage_fast_kernel(const StageProb* __restrict__ probs, const WorkItem* __restrict__ items, StageProb single,
+                       int tiles_per_item) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* buf = reinterpret_cast<u32x4*>(smem);
+  float* red = reinterpret_cast<float*>(smem + 2 * kChunkVecs * 16);
+
+  // Blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of work items so that
+  // the items of one problem (which share Ein) meet in one L2.
+  const int nb = gridDim.x, bx = blockIdx.x;
+  const int xcd = bx & 7;
+  const int item = xcd * (nb >> 3) + min(xcd, nb & 7) + (bx >> 3);
+
+  StageProb p;
+  int tile0, ntl;
+  if (probs) {
+    const WorkItem it = items[item];
+    p = probs[it.prob];
+    tile0 = it.tile0;
+    ntl = it.ntiles;
+  } else {
+    p = single;
+    tile0 = item * tiles_per_item;
+    ntl = min(tiles_per_item, single.ntiles - tile0);
+  }
+  if (ntl == 4 * R)
+    run_item<R, true>(p, tile0, ntl, buf, red);
+  else
+    run_item<R, false>(p, tile0, ntl, buf, red);
+}
+
+template <int R>
 static int launch_r(const StageProb* probs_dev, const WorkItem* items_dev, int nblocks, int tiles_per_item,
                     const StageProb* single, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mfma_kernel<R>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_fast_kernel<R>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kFastSmemBytes);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(stage_mfma_kernel<R>, dim3((unsigned)nblocks), dim3(256), kSmemBytes, s, probs_dev, items_dev,
-                     *single, tiles_per_item);
+  hipLaunchKernelGGL(stage_fast_kernel<R>, dim3((unsigned)nblocks), dim3(256), kFastSmemBytes, s, probs_dev,
+                     items_dev, *single, tiles_per_item);
   return (int)hipGetLastError();
+}
+
+bool stage_is_fast(const StageProb& p) {
+  if (p.l != 16 || p.env_dt != MDBF_F16 || (p.K & 7) != 0) return false;
+  const int64_t row_bytes = p.vin_ld * (int64_t)dtype_size(p.vin_dt);
+  return (row_bytes & 15) == 0;
 }
 
 int mfma_tiles_per_item(long total_tiles) {
   // aim at >= 2 workgroups per compute unit (256 CUs) before growing the per-wave tile count
   long want = total_tiles / 512;
   int tpi = 4;
-  while (tpi < 32 && tpi < want) tpi *= 2;
+  while (tpi < 16 && tpi < want) tpi *= 2;
   return tpi;
 }
 
@@ -251,7 +361,6 @@ int launch_stage_mfma(const StageProb* probs_dev, const WorkItem* items_dev, int
     case 4: return launch_r<1>(probs_dev, items_dev, nblocks, tiles_per_item, single, s);
     case 8: return launch_r<2>(probs_dev, items_dev, nblocks, tiles_per_item, single, s);
     case 16: return launch_r<4>(probs_dev, items_dev, nblocks, tiles_per_item, single, s);
-    case 32: return launch_r<8>(probs_dev, items_dev, nblocks, tiles_per_item, single, s);
     default: return (int)hipErrorInvalidValue;
   }
 }
