@@ -60,9 +60,10 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB_PATH):
+    path = os.environ.get("MDBF_LIB_PATH", _build.LIB_PATH)  # override: an alternative build of this library
+    if path == _build.LIB_PATH and not os.path.exists(path):
         _build.build_library()
-    L = C.CDLL(_build.LIB_PATH)
+    L = C.CDLL(path)
     L.mdbf_bpw.restype = C.c_double
     L.mdbf_bpw.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
     L.mdbf_rank_for_budget.restype = C.c_int

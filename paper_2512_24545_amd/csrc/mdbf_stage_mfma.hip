@@ -38,6 +38,14 @@ typedef const MDBF_GLOBAL _Float16* g_f16_ptr;
 typedef const MDBF_GLOBAL uint16_t* g_u16_ptr;
 typedef const MDBF_GLOBAL float* g_f32_ptr;
 
+#ifdef MDBF_DBG_TIMING
+__device__ unsigned long long g_dbg_time[64 * 64];   // [block < 64][slot]
+#define DBG_T(slot) do { if (blockIdx.x < 64 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == 1) \
+    g_dbg_time[blockIdx.x * 64 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define DBG_T(slot) do {} while (0)
+#endif
+
 constexpr int CB = 8;                      // 128-column blocks per LDS chunk
 constexpr int kChunkVecs = CB * 4 * 64;    // 16-byte vectors per chunk buffer (32 KB)
 constexpr int kFastSmemBytes = 2 * kChunkVecs * 16 + 4 * 16 * 4;
@@ -83,38 +91,35 @@ struct StageRegs {
 };
 
 // Thread (oo = tid/2, ch = tid%2) stages the octet of columns `kcol..kcol+7` for modes 8ch..8ch+7.
+// Octets at or beyond K read the (valid) first octet instead and get zero activations: no branch.
 __device__ __forceinline__ void stage_load(g_u32x4_ptr ein_thr, const void* vin_row, int vin_dt, int kcol, int K,
                                            StageRegs& sr) {
-  if (kcol < K) {
-    g_u32x4_ptr ep = ein_thr + (size_t)kcol * 2;
+  const bool valid = kcol < K;
+  const int kc = valid ? kcol : 0;
+  g_u32x4_ptr ep = ein_thr + (size_t)kc * 2;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sr.e[e] = ep[2 * e];
-    if (vin_dt == MDBF_F32) {
-      g_f32x4_ptr xp = (g_f32x4_ptr)((g_f32_ptr)vin_row + kcol);
-      const floatx4 x0 = xp[0], x1 = xp[1];
-      sr.x[0] = x0.x; sr.x[1] = x0.y; sr.x[2] = x0.z * 0.5f; sr.x[3] = x0.w * 0.5f;
-      sr.x[4] = x1.x * 0.25f; sr.x[5] = x1.y * 0.25f; sr.x[6] = x1.z * 0.125f; sr.x[7] = x1.w * 0.125f;
-    } else if (vin_dt == MDBF_F16) {
-      const u32x4 xb = *(g_u32x4_ptr)((g_f16_ptr)vin_row + kcol);
-      const half8 xh = __builtin_bit_cast(half8, xb);
+  for (int e = 0; e < 8; ++e) sr.e[e] = ep[2 * e];
+  if (vin_dt == MDBF_F32) {
+    g_f32x4_ptr xp = (g_f32x4_ptr)((g_f32_ptr)vin_row + kc);
+    const floatx4 x0 = xp[0], x1 = xp[1];
+    sr.x[0] = x0.x; sr.x[1] = x0.y; sr.x[2] = x0.z * 0.5f; sr.x[3] = x0.w * 0.5f;
+    sr.x[4] = x1.x * 0.25f; sr.x[5] = x1.y * 0.25f; sr.x[6] = x1.z * 0.125f; sr.x[7] = x1.w * 0.125f;
+  } else if (vin_dt == MDBF_F16) {
+    const u32x4 xb = *(g_u32x4_ptr)((g_f16_ptr)vin_row + kc);
+    const half8 xh = __builtin_bit_cast(half8, xb);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sr.x[e] = (float)xh[e] * (1.0f / (float)(1 << (e >> 1)));
-    } else {
-      const u32x4 xb = *(g_u32x4_ptr)((g_u16_ptr)vin_row + kcol);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t wd = xb[e >> 1];
-        const uint32_t bits = (e & 1) ? (wd & 0xFFFF0000u) : (wd << 16);
-        sr.x[e] = __builtin_bit_cast(float, bits) * (1.0f / (float)(1 << (e >> 1)));
-      }
-    }
+    for (int e = 0; e < 8; ++e) sr.x[e] = (float)xh[e] * (1.0f / (float)(1 << (e >> 1)));
   } else {
+    const u32x4 xb = *(g_u32x4_ptr)((g_u16_ptr)vin_row + kc);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      sr.e[e] = u32x4{0u, 0u, 0u, 0u};
-      sr.x[e] = 0.f;
+      const uint32_t wd = xb[e >> 1];
+      const uint32_t bits = (e & 1) ? (wd & 0xFFFF0000u) : (wd << 16);
+      sr.x[e] = __builtin_bit_cast(float, bits) * (1.0f / (float)(1 << (e >> 1)));
     }
   }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) sr.x[e] = valid ? sr.x[e] : 0.f;
 }
 
 // dst: the thread's 8 consecutive 16-byte slots (modes 8ch..8ch+7 of its octet); slot cc is stored at
@@ -135,45 +140,57 @@ __device__ __forceinline__ void stage_store(const StageRegs& sr, u32x4* dst, int
   }
 }
 
-template <int R, bool FULL>
-__device__ __forceinline__ void contract_block(const u32x4* __restrict__ blk_even, const u32x4* __restrict__ blk_odd,
-                                               bool do_virtual, const uint32_t (&word)[R], int nt,
-                                               floatx4 (&acc)[R][2], floatx4 (&accv)[2]) {
-  half8 bop[4];
-#pragma unroll
-  for (int f = 0; f < 4; ++f) {
-    const u32x4 t = (f & 1) ? blk_odd[f * 64] : blk_even[f * 64];
-    bop[f] = __builtin_bit_cast(half8, t);
-  }
-#pragma unroll
-  for (int f = 0; f < 4; ++f) {
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      if (FULL || r < nt) {
-        const uint32_t src = (f < 2) ? word[r] : (word[r] >> 8);
-        acc[r][f & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(expand(src, f & 1), bop[f], acc[r][f & 1], 0, 0, 0);
-      }
-    }
-  }
-  if (do_virtual) {
-#pragma unroll
-    for (int f = 0; f < 4; ++f)
-      accv[f & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(expand(0xFFFFFFFFu, f & 1), bop[f], accv[f & 1], 0, 0, 0);
-  }
+// B operands of one block: the four MFMA steps plus this wave's share of the virtual row.
+struct BlockOps {
+  u32x4 v[5];
+};
+
+__device__ __forceinline__ void load_block_ops(const u32x4* __restrict__ blk, int rd_even, int rd_odd, int rd_virt,
+                                               BlockOps& o) {
+  o.v[0] = blk[rd_even];
+  o.v[1] = blk[64 + rd_odd];
+  o.v[2] = blk[128 + rd_even];
+  o.v[3] = blk[192 + rd_odd];
+  o.v[4] = blk[rd_virt];
 }
 
-template <int R, bool FULL>
+template <int R>
+__device__ __forceinline__ void contract_block(const BlockOps& o, const half8 avirt, const uint32_t (&word)[R],
+                                               floatx4 (&acc)[R][2], floatx4& accv) {
+  uint32_t hi[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) hi[r] = word[r] >> 8;
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+    const half8 bop = __builtin_bit_cast(half8, o.v[f]);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const uint32_t src = (f < 2) ? word[r] : hi[r];
+      acc[r][f & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(expand(src, f & 1), bop, acc[r][f & 1], 0, 0, 0);
+    }
+  }
+  accv = __builtin_amdgcn_mfma_f32_16x16x32_f16(avirt, __builtin_bit_cast(half8, o.v[4]), accv, 0, 0, 0);
+}
+
+template <int R>
 __device__ __forceinline__ void run_item(const StageProb& p, const int tile0, const int ntl, u32x4* buf, float* red) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int nt = (ntl - wave + 3) / 4;   // tiles of this wave: tile0 + wave + 4*jj, jj < nt
-  nt = nt < 0 ? 0 : (nt > R ? R : nt);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
   const int KB = p.KB, NG = KB >> 2, TB = KB & 3;
   const int nchunks = (KB + CB - 1) / CB;
 
-  // sign words: 16-byte vectors, this lane's slot of its wave's first tile
-  const int tstride = 4 * KB * 16;  // vectors between consecutive tiles of one wave
-  g_u32x4_ptr sp = (g_u32x4_ptr)p.S + (size_t)(tile0 + wave) * (size_t)(KB * 16) + lane;
-  g_u32_ptr stail = (g_u32_ptr)p.S + (size_t)(tile0 + wave) * (size_t)(KB * 64) + (size_t)NG * 256 + lane;
+  // Tiles of this wave: tile0 + wave + 4*r.  Tiles past the end of the item are replaced by the
+  // item's last tile (their results are not stored), which keeps the contraction loop branch-free.
+  int trel[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) trel[r] = min(wave + 4 * r, ntl - 1);
+  g_u32x4_ptr sp[R];
+  g_u32_ptr stail[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    sp[r] = (g_u32x4_ptr)p.S + (size_t)(tile0 + trel[r]) * (size_t)(KB * 16) + lane;
+    stail[r] = (g_u32_ptr)p.S + (size_t)(tile0 + trel[r]) * (size_t)(KB * 64) + (size_t)NG * 256 + lane;
+  }
 
   // staging role of this thread
   const int ch = tid & 1, oo = tid >> 1;
@@ -187,39 +204,46 @@ __device__ __forceinline__ void run_item(const StageProb& p, const int tile0, co
   const int kg = lane >> 4, n = lane & 15;
   const int rd_even = kg * 16 + ((n & 8) | ((n & 7) ^ (kg & 7)));
   const int rd_odd = kg * 16 + ((n & 8) | ((n & 7) ^ ((kg + 4) & 7)));
+  // the virtual all-ones row: wave w contracts MFMA step f == w of every block (class w & 1)
+  const int rd_virt = wave * 64 + ((wave & 1) ? rd_odd : rd_even);
+  const half8 avirt = (wave & 1) ? expand(0xFFFFFFFFu, 1) : expand(0xFFFFFFFFu, 0);
+  const float virt_scale = (wave & 1) ? 1048576.f : 16777216.f;  // 2^20 : 2^24
 
   for (int b = 0; b < p.T; ++b) {
     const void* vin_row = (const char*)p.vin + (size_t)b * (size_t)p.vin_ld * (size_t)dtype_size(p.vin_dt);
     floatx4 acc[R][2];
-    floatx4 accv[2];
+    floatx4 accv = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       acc[r][0] = floatx4{0.f, 0.f, 0.f, 0.f};
       acc[r][1] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    accv[0] = floatx4{0.f, 0.f, 0.f, 0.f};
-    accv[1] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     u32x4 wn[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) wn[r] = u32x4{0u, 0u, 0u, 0u};
     if (NG > 0) {
 #pragma unroll
-      for (int r = 0; r < R; ++r)
-        if (FULL || r < nt) wn[r] = sp[r * tstride];
+      for (int r = 0; r < R; ++r) wn[r] = sp[r][0];
     }
 
     StageRegs sr;
+    DBG_T(0);
     stage_load(ein_thr, vin_row, p.vin_dt, st_col, p.K, sr);
     stage_store(sr, buf + st_vec, st_sw);
+    DBG_T(1);
     __syncthreads();
+    DBG_T(2);
 
 #pragma unroll 1
     for (int c = 0; c < nchunks; ++c) {
       const u32x4* bufc = buf + (c & 1) * kChunkVecs;
       const bool more = (c + 1 < nchunks);
+      DBG_T(3 + 4 * c);
+#ifndef MDBF_DBG_NOSTAGE
       if (more) stage_load(ein_thr, vin_row, p.vin_dt, (c + 1) * (CB * kBlockCols) + st_col, p.K, sr);
-      // ---- full groups of this chunk ---------------------------------------------------------
+#endif
+      // ---- full groups of this chunk; B operands are read from LDS one block ahead ---------------
 #pragma unroll
       for (int gi = 0; gi < CB / 4; ++gi) {
         const int g = c * (CB / 4) + gi;
@@ -227,11 +251,14 @@ __device__ __forceinline__ void run_item(const StageProb& p, const int tile0, co
           u32x4 w[R];
 #pragma unroll
           for (int r = 0; r < R; ++r) w[r] = wn[r];
+#ifndef MDBF_DBG_NOSIGNLOAD
           if (g + 1 < NG) {
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-              if (FULL || r < nt) wn[r] = sp[(g + 1) * 64 + r * tstride];
+            for (int r = 0; r < R; ++r) wn[r] = sp[r][(g + 1) * 64];
           }
+#endif
+          BlockOps ops[4];
+          load_block_ops(bufc + (gi * 4) * 256, rd_even, rd_odd, rd_virt, ops[0]);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             uint32_t word[R];
@@ -240,54 +267,60 @@ __device__ __forceinline__ void run_item(const StageProb& p, const int tile0, co
               const u32x4 t = w[r];
               word[r] = t[j];
             }
-            const u32x4* blk = bufc + (gi * 4 + j) * 256;
-            contract_block<R, FULL>(blk + rd_even, blk + rd_odd, wave == j, word, nt, acc, accv);
+            if (j < 3) load_block_ops(bufc + (gi * 4 + j + 1) * 256, rd_even, rd_odd, rd_virt, ops[j + 1]);
+            __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads of the next block ahead of this block's MFMAs
+            contract_block<R>(ops[j], avirt, word, acc, accv);
           }
         }
       }
       // ---- the 1..3 tail blocks (stored block-major) live in the last chunk ---------------------
       if (TB != 0 && c == nchunks - 1) {
+#pragma unroll 1
         for (int tb = 0; tb < TB; ++tb) {
           const int q = 4 * NG + tb;
           uint32_t word[R];
 #pragma unroll
-          for (int r = 0; r < R; ++r) {
-            word[r] = 0u;
-            if (FULL || r < nt) word[r] = stail[(size_t)r * (size_t)(4 * KB * 64) + tb * 64];
-          }
-          const u32x4* blk = bufc + (q - c * CB) * 256;
-          contract_block<R, FULL>(blk + rd_even, blk + rd_odd, wave == (q & 3), word, nt, acc, accv);
+          for (int r = 0; r < R; ++r) word[r] = stail[r][tb * 64];
+          BlockOps ops;
+          load_block_ops(bufc + (q - c * CB) * 256, rd_even, rd_odd, rd_virt, ops);
+          contract_block<R>(ops, avirt, word, acc, accv);
         }
       }
+      DBG_T(4 + 4 * c);
+#ifndef MDBF_DBG_NOSTAGE
       if (more) stage_store(sr, buf + ((c + 1) & 1) * kChunkVecs + st_vec, st_sw);
+#endif
+      DBG_T(5 + 4 * c);
       __syncthreads();
+      DBG_T(6 + 4 * c);
     }
+    DBG_T(40);
 
     // ---- column sums of xs from the virtual all-ones row (all its output rows are equal) --------
-    if (lane < 16) red[wave * 16 + lane] = accv[0][0] * 16777216.f + accv[1][0] * 1048576.f;  // 2^24, 2^20
+    if (lane < 16) red[wave * 16 + lane] = accv[0] * virt_scale;
     __syncthreads();
     const float colsum = (red[n] + red[16 + n]) + (red[32 + n] + red[48 + n]);
 
     // ---- fix-up, envelope accumulate, store ----------------------------------------------------
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      if (FULL || r < nt) {
-        const int rowb = (tile0 + wave + 4 * r) * kTileRows + 4 * kg;
-        float ev[4];
+      const bool tile_ok = (wave + 4 * r) < ntl;
+      const int rowb = (tile0 + trel[r]) * kTileRows + 4 * kg;
+      float ev[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = rowb + i;
-          ev[i] = (row < p.rows) ? (float)((g_f16_ptr)p.Eout)[(size_t)row * 16 + n] : 0.f;
-        }
+      for (int i = 0; i < 4; ++i) {
+        const int row = min(rowb + i, p.rows - 1);
+        ev[i] = (float)((g_f16_ptr)p.Eout)[(size_t)row * 16 + n];
+      }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = rowb + i;
-          const float P = colsum - acc[r][0][i] * 33554432.f - acc[r][1][i] * 2097152.f;  // 2^25, 2^21
-          const float v = row16_sum(ev[i] * P);
-          if (n == 0 && row < p.rows) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, v);
-        }
+      for (int i = 0; i < 4; ++i) {
+        const int row = rowb + i;
+        const float P = colsum - acc[r][0][i] * 33554432.f - acc[r][1][i] * 2097152.f;  // 2^25, 2^21
+        const float v = row16_sum(ev[i] * P);
+        if (tile_ok && n == 0 && row < p.rows) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, v);
       }
     }
+    DBG_T(41);
     __syncthreads();  // red and the chunk buffers are reused by the next token
   }
 }
@@ -318,10 +351,7 @@ void stage_fast_kernel(const StageProb* __restrict__ probs, const WorkItem* __re
     tile0 = item * tiles_per_item;
     ntl = min(tiles_per_item, single.ntiles - tile0);
   }
-  if (ntl == 4 * R)
-    run_item<R, true>(p, tile0, ntl, buf, red);
-  else
-    run_item<R, false>(p, tile0, ntl, buf, red);
+  run_item<R>(p, tile0, ntl, buf, red);
 }
 
 template <int R>
@@ -338,6 +368,12 @@ static int launch_r(const StageProb* probs_dev, const WorkItem* items_dev, int n
                      items_dev, *single, tiles_per_item);
   return (int)hipGetLastError();
 }
+
+#ifdef MDBF_DBG_TIMING
+extern "C" int mdbf_dbg_read(void* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_time), bytes < sizeof(g_dbg_time) ? bytes : sizeof(g_dbg_time));
+}
+#endif
 
 bool stage_is_fast(const StageProb& p) {
   if (p.l != 16 || p.env_dt != MDBF_F16 || (p.K & 7) != 0) return false;
