@@ -256,6 +256,8 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
       if (!stage_is_fast(sp[s])) fast[s] = 0;
       for (int t0 = 0; t0 < sp[s].ntiles; t0 += tpi) {
         WorkItem w;
+        memset(&w, 0, sizeof(w));
+        w.p = sp[s];
         w.prob = i;
         w.tile0 = t0;
         w.ntiles = sp[s].ntiles - t0 < tpi ? sp[s].ntiles - t0 : tpi;

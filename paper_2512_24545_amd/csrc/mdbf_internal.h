@@ -18,11 +18,8 @@ namespace mdbf {
 // so that, with u = w >> 8*(f/2), the word  u & ((1<<(4c+i)) | (1<<(4c+i+16))),  c = f%2,
 // viewed as two fp16 values, holds the entries (e = 2i, 2i+1) as {0 or 2^(4c+i-24)}: the
 // operand of one matrix-core step costs one AND per register and no shift.
-// Blocks of a tile are stored in groups of four, lane-major inside a group (a lane's four
-// words are 16 contiguous bytes); the last 0..3 blocks of a tile are stored block-major.
-// Word offset of (tile t, block q, lane L), KB = blocks per tile, NG = KB/4:
-//   q < 4*NG :  t*KB*64 + (q/4)*256 + L*4 + q%4
-//   else     :  t*KB*64 + NG*256 + (q-4*NG)*64 + L
+// Blocks of a tile are stored one after the other (256 contiguous bytes each, one word per lane):
+//   word offset of (tile t, block q, lane L), KB = blocks per tile:  (t*KB + q)*64 + L
 // Padding rows/columns hold bit 0.
 // ---------------------------------------------------------------------------------------
 constexpr int kTileRows = 16;
@@ -34,10 +31,7 @@ __host__ __device__ inline size_t packed_words(int rows, int cols) {
   return (size_t)num_tiles(rows) * (size_t)num_blocks(cols) * 64u;
 }
 __host__ __device__ inline size_t word_offset(int tile, int q, int lane, int KB) {
-  const int NG = KB >> 2;
-  size_t base = (size_t)tile * (size_t)KB * 64u;
-  if (q < 4 * NG) return base + (size_t)(q >> 2) * 256u + (size_t)lane * 4u + (size_t)(q & 3);
-  return base + (size_t)NG * 256u + (size_t)(q - 4 * NG) * 64u + (size_t)lane;
+  return ((size_t)tile * (size_t)KB + (size_t)q) * 64u + (size_t)lane;
 }
 // bit index of local column kl (0..127) inside its lane's word, and the lane's 8-column group
 __host__ __device__ inline int bit_of_local_col(int kl) {
@@ -65,10 +59,14 @@ struct StageProb {
   int32_t pad_;
 };
 
-// A unit of work of the stage kernels: row tiles [tile0, tile0+ntiles) of problem `prob`.
-struct WorkItem {
-  int32_t prob, tile0, ntiles, pad_;
+// A unit of work of the stage kernels: row tiles [tile0, tile0+ntiles) of problem `prob`, with a copy
+// of the problem so that one 128-byte read describes the whole item.
+struct alignas(128) WorkItem {
+  StageProb p;
+  int32_t tile0, ntiles, prob, pad_;
 };
+static_assert(sizeof(StageProb) == 96, "StageProb layout is read dword by dword on the device");
+static_assert(sizeof(WorkItem) == 128, "WorkItem must be 128 bytes");
 
 // Plan of a batched forward (host and device copies are byte-identical).
 struct PlanHeader {

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(64) void stage_precise_kernel(const StageProb* __re
   const StageProb* pp;
   if (probs) {
     // in batch mode every work item is expanded to one block per tile by the launcher
-    const WorkItem it = items[blockIdx.y];
+    const WorkItem& it = items[blockIdx.y];
     if ((int)blockIdx.x >= it.ntiles) return;
     pp = &probs[it.prob];
     tile = it.tile0 + blockIdx.x;

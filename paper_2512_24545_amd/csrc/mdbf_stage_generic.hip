@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void stage_generic_kernel(const StageProb* __r
   const StageProb* pp;
   int tile0, ntl;
   if (probs) {
-    const WorkItem it = items[blockIdx.x];
+    const WorkItem& it = items[blockIdx.x];
     pp = &probs[it.prob];
     tile0 = it.tile0;
     ntl = it.ntiles;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void stage_generic_kernel(const StageProb* __r
   // tiles of this wave: tile0 + wave + 4*jj for jj < nt
   int nt = (ntl - wave + 3) / 4;
   nt = nt < 0 ? 0 : (nt > R ? R : nt);
-  const int KB = p.KB, NG = KB >> 2;
+  const int KB = p.KB;
   const int ngroups = (KB + 3) >> 2;
   const int nchunks = (KB + CB - 1) / CB;
 
@@ -77,23 +77,17 @@ __global__ __launch_bounds__(256) void stage_generic_kernel(const StageProb* __r
   for (int r = 0; r < R; ++r) sbase[r] = p.S + (size_t)(tile0 + wave + 4 * r) * (size_t)KB * 64u;
 
   auto load_group = [&](int g, u32x4 (&w)[R]) {
-    if (g < NG) {
 #pragma unroll
-      for (int r = 0; r < R; ++r)
-        if (r < nt) w[r] = *reinterpret_cast<const u32x4*>(sbase[r] + (size_t)g * 256u + (size_t)lane * 4u);
-    } else {
-      const int nb = KB - 4 * NG;  // 1..3 tail blocks, stored block-major
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        u32x4 t = {0u, 0u, 0u, 0u};
-        if (r < nt) {
-          const uint32_t* tb = sbase[r] + (size_t)NG * 256u + lane;
-          t.x = tb[0];
-          if (nb > 1) t.y = tb[64];
-          if (nb > 2) t.z = tb[128];
-        }
-        w[r] = t;
+    for (int r = 0; r < R; ++r) {
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (r < nt) {
+        const uint32_t* tb = sbase[r] + (size_t)(4 * g) * 64u + lane;
+        t.x = tb[0];
+        if (4 * g + 1 < KB) t.y = tb[64];
+        if (4 * g + 2 < KB) t.z = tb[128];
+        if (4 * g + 3 < KB) t.w = tb[192];
       }
+      w[r] = t;
     }
   };
 

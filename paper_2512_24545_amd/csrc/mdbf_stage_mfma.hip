@@ -1,17 +1,18 @@
 // Matrix-core evaluation of one envelope-scaled binary product on gfx950: the FAST variant
-// (l == 16, fp16 envelopes, K a multiple of 8, 16-byte aligned activation rows).
+// (l == 16, fp16 envelopes, K >= 897 and a multiple of 8, 16-byte aligned activation rows).
 //
 //   out[r] = sum_c Eout[r,c] * P[r,c],     P[r,c] = sum_j S[r,j] * xs[j,c],   xs[j,c] = fp16(Ein[j,c] * vin[j])
 //
 // (paper Eq. "me-dbf-expand": per factor, l envelope-scaled copies of the shared sign basis).
 // P is a skinny GEMM (rows x K) . (K x 16): exactly one 16x16x32 fp16 MFMA tile wide.
 //
-// Work decomposition: a workgroup of four wavefronts owns up to 4*R row tiles (16 rows each) of
-// one problem and the whole contraction; wave w owns tiles w, w+4, ...  The scaled activations xs
-// are staged chunk by chunk (1024 columns) in LDS in the order the MFMA B operand wants them and
-// shared by all tiles of the workgroup; sign words stream from HBM with 128-bit loads, one group
-// (512 columns) ahead of their use; the envelope rows of the next chunk are in flight while the
-// current chunk is contracted.
+// Work decomposition: a unit of work is (up to 4*R row tiles of one problem, one token, the whole
+// contraction).  Workgroups of four wavefronts are persistent: each walks a list of units, and the
+// loads of the next unit (its first sign words, its first chunk of envelope rows) are issued while
+// the current unit finishes, so that no unit starts or ends on an exposed memory latency.
+// Wave w owns tiles w, w+4, ... of the unit.  The scaled activations xs are staged chunk by chunk
+// (1024 columns) in LDS in the order the MFMA B operand wants them and shared by all tiles of the
+// workgroup; sign words stream from HBM one chunk (1024 columns) ahead of their use.
 //
 // Sign expansion without shifts: with bit t=1 meaning -1,  S = 1 - 2t, hence
 //      P[r,c] = colsum[c] - 2 * sum_j t[r,j] xs[j,c].
@@ -21,7 +22,9 @@
 // class c (positions 4c..4c+3) is scaled by 2^(4c-24) exactly, and each class has its own fp32
 // accumulator.  Bits 8..15 of each half word are brought down with one shift per word.
 // colsum comes from the same MFMAs applied to a virtual row whose bits are all 1, so that it sees
-// exactly the staged (rounded) values; the four waves share that work block by block.
+// exactly the staged (rounded) values; wave w contracts MFMA step f == w of every block for it.
+#include <type_traits>
+
 #include "mdbf_internal.h"
 
 namespace mdbf {
@@ -40,15 +43,21 @@ typedef const MDBF_GLOBAL float* g_f32_ptr;
 
 #ifdef MDBF_DBG_TIMING
 __device__ unsigned long long g_dbg_time[64 * 64];   // [block < 64][slot]
-#define DBG_T(slot) do { if (blockIdx.x < 64 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == 1) \
+#define DBG_T(slot) do { if (dbg_unit == 2 && blockIdx.x < 64 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == 1 && (slot) < 64) \
     g_dbg_time[blockIdx.x * 64 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#define DBG_UNIT_DECL int dbg_unit = 0
+#define DBG_UNIT_NEXT ++dbg_unit
 #else
 #define DBG_T(slot) do {} while (0)
+#define DBG_UNIT_DECL do {} while (0)
+#define DBG_UNIT_NEXT do {} while (0)
 #endif
 
 constexpr int CB = 8;                      // 128-column blocks per LDS chunk
 constexpr int kChunkVecs = CB * 4 * 64;    // 16-byte vectors per chunk buffer (32 KB)
-constexpr int kFastSmemBytes = 2 * kChunkVecs * 16 + 4 * 16 * 4;
+constexpr int kPrefetchBlocks = CB;        // sign words are loaded one chunk (8 blocks) ahead of their use
+__host__ __device__ constexpr int eo_vecs(int R) { return R * 4 * 16 * 2 < 256 ? 256 : R * 4 * 16 * 2; }  // Eout rows of a unit, 16 B each, a multiple of the 256 threads
+__host__ __device__ constexpr int fast_smem_bytes(int R) { return 2 * kChunkVecs * 16 + eo_vecs(R) * 16 + 4 * 16 * 4; }
 
 __device__ __forceinline__ half8 expand(uint32_t src, int c) {
   // class c: bit positions 4c..4c+3 and the same 16 above
@@ -86,45 +95,75 @@ __device__ __forceinline__ float row16_sum(float v) {
 }
 
 struct StageRegs {
-  u32x4 e[8];   // 8 envelope rows of one column octet, 8 fp16 modes each
-  float x[8];   // the octet's 8 activations, already multiplied by 2^-(e/2)
+  u32x4 e[8];    // 8 envelope rows of one column octet, 8 fp16 modes each
+  u32x4 xr[2];   // the octet's 8 activations as loaded (xr[1] differs from xr[0] only for fp32)
+  float vmask;   // 1 if the octet lies inside K, else 0
 };
 
 // Thread (oo = tid/2, ch = tid%2) stages the octet of columns `kcol..kcol+7` for modes 8ch..8ch+7.
-// Octets at or beyond K read the (valid) first octet instead and get zero activations: no branch.
-__device__ __forceinline__ void stage_load(g_u32x4_ptr ein_thr, const void* vin_row, int vin_dt, int kcol, int K,
-                                           StageRegs& sr) {
+// Octets at or beyond K read the (valid) first octet instead and get zero activations.  Only loads
+// are issued here, with no branch around them; nothing waits for them until stage_store.  The loads
+// come in four parts so that the caller can spread them over several block steps.
+struct StageAddr {
+  g_u32x4_ptr ep;                 // first envelope row of the octet, this thread's column half
+  const char MDBF_GLOBAL* xb;     // first activation of the octet
+  int x2off;                      // byte offset of the second activation vector (fp32 only, else 0)
+};
+
+__device__ __forceinline__ void stage_addr(const void* ein, int ch, const void* vin_row, int vin_dt, int kcol, int K,
+                                           StageRegs& sr, StageAddr& sa) {
   const bool valid = kcol < K;
   const int kc = valid ? kcol : 0;
-  g_u32x4_ptr ep = ein_thr + (size_t)kc * 2;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) sr.e[e] = ep[2 * e];
-  if (vin_dt == MDBF_F32) {
-    g_f32x4_ptr xp = (g_f32x4_ptr)((g_f32_ptr)vin_row + kc);
-    const floatx4 x0 = xp[0], x1 = xp[1];
-    sr.x[0] = x0.x; sr.x[1] = x0.y; sr.x[2] = x0.z * 0.5f; sr.x[3] = x0.w * 0.5f;
-    sr.x[4] = x1.x * 0.25f; sr.x[5] = x1.y * 0.25f; sr.x[6] = x1.z * 0.125f; sr.x[7] = x1.w * 0.125f;
-  } else if (vin_dt == MDBF_F16) {
-    const u32x4 xb = *(g_u32x4_ptr)((g_f16_ptr)vin_row + kc);
-    const half8 xh = __builtin_bit_cast(half8, xb);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) sr.x[e] = (float)xh[e] * (1.0f / (float)(1 << (e >> 1)));
-  } else {
-    const u32x4 xb = *(g_u32x4_ptr)((g_u16_ptr)vin_row + kc);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t wd = xb[e >> 1];
-      const uint32_t bits = (e & 1) ? (wd & 0xFFFF0000u) : (wd << 16);
-      sr.x[e] = __builtin_bit_cast(float, bits) * (1.0f / (float)(1 << (e >> 1)));
-    }
+  sr.vmask = valid ? 1.f : 0.f;
+  sa.ep = (g_u32x4_ptr)ein + ((size_t)kc * 2 + ch);
+  const int esz_shift = (vin_dt == MDBF_F32) ? 2 : 1;
+  sa.xb = (const char MDBF_GLOBAL*)vin_row + ((size_t)kc << esz_shift);
+  sa.x2off = (vin_dt == MDBF_F32) ? 16 : 0;
+}
+
+__device__ __forceinline__ void stage_load_part(const StageAddr& sa, int part, StageRegs& sr) {
+  sr.e[2 * part] = sa.ep[4 * part];
+  sr.e[2 * part + 1] = sa.ep[4 * part + 2];
+  if (part == 0) {
+    sr.xr[0] = *(g_u32x4_ptr)sa.xb;
+    sr.xr[1] = *(g_u32x4_ptr)(sa.xb + sa.x2off);
   }
+}
+
+__device__ __forceinline__ void stage_load(const void* ein, int ch, const void* vin_row, int vin_dt, int kcol, int K,
+                                           StageRegs& sr) {
+  StageAddr sa;
+  stage_addr(ein, ch, vin_row, vin_dt, kcol, K, sr, sa);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) sr.x[e] = valid ? sr.x[e] : 0.f;
+  for (int part = 0; part < 4; ++part) stage_load_part(sa, part, sr);
 }
 
 // dst: the thread's 8 consecutive 16-byte slots (modes 8ch..8ch+7 of its octet); slot cc is stored at
 // cc ^ sw so that the 64 lanes of one store instruction spread over all LDS banks.
-__device__ __forceinline__ void stage_store(const StageRegs& sr, u32x4* dst, int sw) {
+__device__ __forceinline__ void stage_store(const StageRegs& sr, int vin_dt, u32x4* dst, int sw) {
+  // activations as fp32, times 2^-(e/2) (the position factor of the sign expansion), times the K mask
+  float x[8];
+  const u32x4 x0 = sr.xr[0], x1 = sr.xr[1];
+  if (vin_dt == MDBF_F32) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t bits = (e < 4) ? x0[e & 3] : x1[e & 3];
+      x[e] = __builtin_bit_cast(float, bits);
+    }
+  } else if (vin_dt == MDBF_F16) {
+    const half8 xh = __builtin_bit_cast(half8, x0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = (float)xh[e];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t wd = x0[e >> 1];
+      const uint32_t bits = (e & 1) ? (wd & 0xFFFF0000u) : (wd << 16);
+      x[e] = __builtin_bit_cast(float, bits);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] *= sr.vmask * (1.0f / (float)(1 << (e >> 1)));
 #pragma unroll
   for (int cc = 0; cc < 8; ++cc) {
     u32x4 v;
@@ -132,8 +171,8 @@ __device__ __forceinline__ void stage_store(const StageRegs& sr, u32x4* dst, int
     for (int i = 0; i < 4; ++i) {
       const u32x4 r0 = sr.e[2 * i], r1 = sr.e[2 * i + 1];
       const uint32_t a0 = r0[cc >> 1], a1 = r1[cc >> 1];
-      const uint32_t pr = (cc & 1) ? mix_pair_hi(a0, a1, sr.x[2 * i], sr.x[2 * i + 1])
-                                   : mix_pair_lo(a0, a1, sr.x[2 * i], sr.x[2 * i + 1]);
+      const uint32_t pr = (cc & 1) ? mix_pair_hi(a0, a1, x[2 * i], x[2 * i + 1])
+                                   : mix_pair_lo(a0, a1, x[2 * i], x[2 * i + 1]);
       v[i] = pr;
     }
     dst[cc ^ sw] = v;
@@ -172,25 +211,108 @@ __device__ __forceinline__ void contract_block(const BlockOps& o, const half8 av
   accv = __builtin_amdgcn_mfma_f32_16x16x32_f16(avirt, __builtin_bit_cast(half8, o.v[4]), accv, 0, 0, 0);
 }
 
+// Makes the compiler wait, here, for the sign words that were loaded by an earlier loop iteration:
+// across loop boundaries it cannot count which loads are still in flight and would otherwise wait
+// for ALL outstanding loads at every later first use, including the ones just issued.
 template <int R>
-__device__ __forceinline__ void run_item(const StageProb& p, const int tile0, const int ntl, u32x4* buf, float* red) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
-  const int KB = p.KB, NG = KB >> 2, TB = KB & 3;
-  const int nchunks = (KB + CB - 1) / CB;
-
-  // Tiles of this wave: tile0 + wave + 4*r.  Tiles past the end of the item are replaced by the
-  // item's last tile (their results are not stored), which keeps the contraction loop branch-free.
-  int trel[R];
+__device__ __forceinline__ void settle(uint32_t (&wq)[R][kPrefetchBlocks]) {
 #pragma unroll
-  for (int r = 0; r < R; ++r) trel[r] = min(wave + 4 * r, ntl - 1);
-  g_u32x4_ptr sp[R];
-  g_u32_ptr stail[R];
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int j = 0; j < kPrefetchBlocks; ++j) asm volatile("" : "+v"(wq[r][j]));
+}
+
+// Wave-uniform description of a unit.  sbase[r] is the first sign word of the r-th tile of this wave.
+template <int R>
+struct Unit {
+  StageProb p;
+  int tile0, ntl, b, item;
+  const uint32_t* sbase[R];
+  const void* vin_row;
+};
+
+template <int R>
+__device__ __forceinline__ void finish_unit(Unit<R>& u, int wave) {
+  // Tiles of this wave: tile0 + wave + 4*r.  Tiles past the end of the unit are replaced by the unit's
+  // last tile (their results are not stored), which keeps the contraction loop free of branches.
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    sp[r] = (g_u32x4_ptr)p.S + (size_t)(tile0 + trel[r]) * (size_t)(KB * 16) + lane;
-    stail[r] = (g_u32_ptr)p.S + (size_t)(tile0 + trel[r]) * (size_t)(KB * 64) + (size_t)NG * 256 + lane;
+    const int trel = min(wave + 4 * r, u.ntl - 1);
+    u.sbase[r] = u.p.S + (size_t)(u.tile0 + trel) * (size_t)(u.p.KB * 64);
   }
+  u.vin_row = (const char*)u.p.vin + (size_t)u.b * (size_t)u.p.vin_ld * (size_t)dtype_size(u.p.vin_dt);
+}
+
+// In batch mode the 128-byte work item is fetched one dword per lane and broadcast to scalar registers
+// later; a single call derives its units arithmetically.
+__device__ __forceinline__ uint32_t fetch_desc(const WorkItem* __restrict__ items, int item, int lane) {
+  return ((g_u32_ptr)(items + item))[lane & 31];
+}
+
+template <int R, bool BATCH>
+__device__ __forceinline__ void make_unit(uint32_t desc, const StageProb& single, int tiles_per_item, int item,
+                                          int wave, Unit<R>& u) {
+  if (BATCH) {
+    uint32_t d[26];
+#pragma unroll
+    for (int i = 0; i < 26; ++i) d[i] = __builtin_amdgcn_readlane(desc, i);
+    auto ptr = [&](int i) { return (uint64_t)d[i] | ((uint64_t)d[i + 1] << 32); };
+    u.p.S = (const uint32_t*)ptr(0);
+    u.p.Ein = (const void*)ptr(2);
+    u.p.Eout = (const void*)ptr(4);
+    u.p.vin = (const void*)ptr(6);
+    u.p.out = (void*)ptr(8);
+    u.p.vin_ld = (int64_t)ptr(10);
+    u.p.out_ld = (int64_t)ptr(12);
+    u.p.rows = (int)d[14];
+    u.p.K = (int)d[15];
+    u.p.l = (int)d[16];
+    u.p.T = (int)d[17];
+    u.p.KB = (int)d[18];
+    u.p.ntiles = (int)d[19];
+    u.p.env_dt = (int)d[20];
+    u.p.vin_dt = (int)d[21];
+    u.p.out_dt = (int)d[22];
+    u.p.pad_ = 0;
+    u.tile0 = (int)d[24];
+    u.ntl = (int)d[25];
+  } else {
+    u.p = single;
+    u.tile0 = item * tiles_per_item;
+    u.ntl = min(tiles_per_item, single.ntiles - u.tile0);
+  }
+  u.item = item;
+  u.b = 0;
+  finish_unit<R>(u, wave);
+}
+
+template <int R, bool BATCH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single, int tiles_per_item) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* buf = reinterpret_cast<u32x4*>(smem);
+  u32x4* eo = reinterpret_cast<u32x4*>(smem + 2 * kChunkVecs * 16);
+  float* red = reinterpret_cast<float*>(smem + 2 * kChunkVecs * 16 + eo_vecs(R) * 16);
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
+
+  // ---- the units of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a
+  // contiguous range of items, walked by its workgroups side by side, so that the items of one problem
+  // (which share Ein) meet in one L2 at about the same time.
+  int item, i_hi, stride;
+  if ((gridDim.x & 7) == 0) {
+    const int xcd = blockIdx.x & 7;
+    const int i_lo = (int)(((long)nitems * xcd) >> 3);
+    i_hi = (int)(((long)nitems * (xcd + 1)) >> 3);
+    stride = gridDim.x >> 3;
+    item = i_lo + (blockIdx.x >> 3);
+  } else {
+    i_hi = nitems;
+    stride = gridDim.x;
+    item = blockIdx.x;
+  }
+  if (item >= i_hi) return;
 
   // staging role of this thread
   const int ch = tid & 1, oo = tid >> 1;
@@ -198,7 +320,6 @@ __device__ __forceinline__ void run_item(const StageProb& p, const int tile0, co
   const int st_col = st_q * kBlockCols + st_f * 32 + st_kg * 8;            // column inside a chunk
   const int st_vec = (st_q * 4 + st_f) * 64 + st_kg * 16 + ch * 8;         // first of its 8 LDS slots
   const int st_sw = (st_kg + 4 * (st_f & 1)) & 7;
-  g_u32x4_ptr ein_thr = (g_u32x4_ptr)p.Ein + ch;
 
   // B-operand read slots of this lane (same swizzle as the stores)
   const int kg = lane >> 4, n = lane & 15;
@@ -209,8 +330,40 @@ __device__ __forceinline__ void run_item(const StageProb& p, const int tile0, co
   const half8 avirt = (wave & 1) ? expand(0xFFFFFFFFu, 1) : expand(0xFFFFFFFFu, 0);
   const float virt_scale = (wave & 1) ? 1048576.f : 16777216.f;  // 2^20 : 2^24
 
-  for (int b = 0; b < p.T; ++b) {
-    const void* vin_row = (const char*)p.vin + (size_t)b * (size_t)p.vin_ld * (size_t)dtype_size(p.vin_dt);
+  Unit<R> u;
+  {
+    uint32_t desc0 = 0;
+    if (BATCH) desc0 = fetch_desc(items, item, lane);
+    make_unit<R, BATCH>(desc0, single, tiles_per_item, item, wave, u);
+  }
+
+  // ---- prologue: first sign words and first chunk of the first unit
+  uint32_t wq[R][kPrefetchBlocks];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int j = 0; j < kPrefetchBlocks; ++j)
+      wq[r][j] = ((g_u32_ptr)(u.sbase[r] + j * 64))[lane];   // KB >= 8 for every fast problem
+  StageRegs sr;
+  stage_load(u.p.Ein, ch, u.vin_row, u.p.vin_dt, st_col, u.p.K, sr);
+  int par = 0;
+  stage_store(sr, u.p.vin_dt, buf + st_vec, st_sw);
+  __syncthreads();
+
+  DBG_UNIT_DECL;
+  for (;;) {
+    DBG_UNIT_NEXT;
+    DBG_T(0);
+    settle<R>(wq);
+    // ---- which unit comes next: the next token of the same item, else this workgroup's next item,
+    //      whose descriptor is requested now and only looked at when this unit's last chunk starts
+    const bool next_token = (u.b + 1 < u.p.T);
+    const int ni = u.item + stride;
+    const bool has_next = next_token || (ni < i_hi);
+    uint32_t desc_next = 0;
+    if (BATCH) desc_next = fetch_desc(items, min(ni, nitems - 1), lane);
+    Unit<R> un = u;
+
     floatx4 acc[R][2];
     floatx4 accv = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -219,154 +372,169 @@ __device__ __forceinline__ void run_item(const StageProb& p, const int tile0, co
       acc[r][1] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    u32x4 wn[R];
+    const int KB = u.p.KB;
+    const int nchunks = (KB + CB - 1) / CB;
+
+    // ---- all chunks but the last.  The sign words and the envelope rows of the next chunk are requested
+    //      up front, into registers of their own, and have the whole chunk to arrive; blocks that do
+    //      not exist are replaced by a harmless reload of block 0 so that no branch surrounds a load.
+    uint32_t wnext[R][kPrefetchBlocks];
+#pragma unroll 1
+    for (int c = 0; c < nchunks - 1; ++c) {
+      StageAddr sa;
+      stage_addr(u.p.Ein, ch, u.vin_row, u.p.vin_dt, (c + 1) * (CB * kBlockCols) + st_col, u.p.K, sr, sa);
+      DBG_T(1 + 4 * c);
+      const u32x4* bufc = buf + par * kChunkVecs;
 #pragma unroll
-    for (int r = 0; r < R; ++r) wn[r] = u32x4{0u, 0u, 0u, 0u};
-    if (NG > 0) {
+      for (int jj = 0; jj < CB; ++jj) {
+        if (jj < 4) {
+          // a quarter of the next chunk's loads per step: they are all at least four steps old when
+          // the chunk ends, and they do not arrive at the memory pipeline in one burst
 #pragma unroll
-      for (int r = 0; r < R; ++r) wn[r] = sp[r][0];
+          for (int j = 2 * jj; j < 2 * jj + 2; ++j) {
+            const int qn = (c + 1) * CB + j;
+            const uint64_t off = (qn < KB) ? (uint64_t)qn * 256u : 0u;
+#pragma unroll
+            for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)((uint64_t)u.sbase[r] + off))[lane];
+          }
+          stage_load_part(sa, jj, sr);
+        }
+        uint32_t word[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) word[r] = wq[r][jj];
+        BlockOps ops;
+        load_block_ops(bufc + jj * 256, rd_even, rd_odd, rd_virt, ops);
+        contract_block<R>(ops, avirt, word, acc, accv);
+      }
+      DBG_T(2 + 4 * c);
+#ifndef MDBF_DBG_NOSTAGE
+      stage_store(sr, u.p.vin_dt, buf + (par ^ 1) * kChunkVecs + st_vec, st_sw);
+#endif
+      DBG_T(3 + 4 * c);
+      __syncthreads();
+      DBG_T(4 + 4 * c);
+      par ^= 1;
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < kPrefetchBlocks; ++j) wq[r][j] = wnext[r][j];
     }
 
-    StageRegs sr;
-    DBG_T(0);
-    stage_load(ein_thr, vin_row, p.vin_dt, st_col, p.K, sr);
-    stage_store(sr, buf + st_vec, st_sw);
-    DBG_T(1);
-    __syncthreads();
-    DBG_T(2);
-
-#pragma unroll 1
-    for (int c = 0; c < nchunks; ++c) {
-      const u32x4* bufc = buf + (c & 1) * kChunkVecs;
-      const bool more = (c + 1 < nchunks);
-      DBG_T(3 + 4 * c);
-#ifndef MDBF_DBG_NOSTAGE
-      if (more) stage_load(ein_thr, vin_row, p.vin_dt, (c + 1) * (CB * kBlockCols) + st_col, p.K, sr);
-#endif
-      // ---- full groups of this chunk; B operands are read from LDS one block ahead ---------------
-#pragma unroll
-      for (int gi = 0; gi < CB / 4; ++gi) {
-        const int g = c * (CB / 4) + gi;
-        if (g < NG) {
-          u32x4 w[R];
-#pragma unroll
-          for (int r = 0; r < R; ++r) w[r] = wn[r];
-#ifndef MDBF_DBG_NOSIGNLOAD
-          if (g + 1 < NG) {
-#pragma unroll
-            for (int r = 0; r < R; ++r) wn[r] = sp[r][(g + 1) * 64];
-          }
-#endif
-          BlockOps ops[4];
-          load_block_ops(bufc + (gi * 4) * 256, rd_even, rd_odd, rd_virt, ops[0]);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            uint32_t word[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-              const u32x4 t = w[r];
-              word[r] = t[j];
-            }
-            if (j < 3) load_block_ops(bufc + (gi * 4 + j + 1) * 256, rd_even, rd_odd, rd_virt, ops[j + 1]);
-            __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads of the next block ahead of this block's MFMAs
-            contract_block<R>(ops[j], avirt, word, acc, accv);
-          }
-        }
+    // ---- the last chunk.  All loads of the next unit (its first chunk of sign words and of envelope
+    //      rows) and this unit's Eout rows are issued up front, into registers of their own, so that
+    //      they have a whole chunk of contraction time to arrive.
+    {
+      const int c = nchunks - 1;
+      settle<R>(wq);
+      asm volatile("" : "+v"(desc_next));
+      if (next_token) {
+        un.b = u.b + 1;
+        finish_unit<R>(un, wave);
+      } else if (has_next) {
+        make_unit<R, BATCH>(desc_next, single, tiles_per_item, ni, wave, un);
       }
-      // ---- the 1..3 tail blocks (stored block-major) live in the last chunk ---------------------
-      if (TB != 0 && c == nchunks - 1) {
-#pragma unroll 1
-        for (int tb = 0; tb < TB; ++tb) {
-          const int q = 4 * NG + tb;
+      StageAddr sa;
+      stage_addr(un.p.Ein, ch, un.vin_row, un.p.vin_dt, st_col, un.p.K, sr, sa);
+      u32x4 eoreg[eo_vecs(R) / 256];
+#pragma unroll
+      for (int t = 0; t < eo_vecs(R) / 256; ++t) {
+        const int v = tid + 256 * t;
+        const int row = min(u.tile0 * kTileRows + (v >> 1), u.p.rows - 1);
+        eoreg[t] = ((g_u32x4_ptr)u.p.Eout)[(size_t)row * 2 + (v & 1)];
+      }
+      DBG_T(1 + 4 * c);
+      const u32x4* bufc = buf + par * kChunkVecs;
+#pragma unroll
+      for (int jj = 0; jj < CB; ++jj) {
+        if (jj < 4) {
+#pragma unroll
+          for (int j = 2 * jj; j < 2 * jj + 2; ++j)
+#pragma unroll
+            for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)(un.sbase[r] + j * 64))[lane];
+          stage_load_part(sa, jj, sr);
+        }
+        if (c * CB + jj < KB) {
           uint32_t word[R];
 #pragma unroll
-          for (int r = 0; r < R; ++r) word[r] = stail[r][tb * 64];
+          for (int r = 0; r < R; ++r) word[r] = wq[r][jj];
           BlockOps ops;
-          load_block_ops(bufc + (q - c * CB) * 256, rd_even, rd_odd, rd_virt, ops);
+          load_block_ops(bufc + jj * 256, rd_even, rd_odd, rd_virt, ops);
           contract_block<R>(ops, avirt, word, acc, accv);
         }
       }
-      DBG_T(4 + 4 * c);
+      DBG_T(2 + 4 * c);
+      red[wave * 16 + n] = accv[0] * virt_scale;   // all output rows of the virtual tile are equal
+#pragma unroll
+      for (int t = 0; t < eo_vecs(R) / 256; ++t) eo[tid + 256 * t] = eoreg[t];
 #ifndef MDBF_DBG_NOSTAGE
-      if (more) stage_store(sr, buf + ((c + 1) & 1) * kChunkVecs + st_vec, st_sw);
+      stage_store(sr, un.p.vin_dt, buf + (par ^ 1) * kChunkVecs + st_vec, st_sw);
 #endif
-      DBG_T(5 + 4 * c);
+      DBG_T(3 + 4 * c);
       __syncthreads();
-      DBG_T(6 + 4 * c);
+      DBG_T(4 + 4 * c);
+      par ^= 1;
     }
+
+    // ---- epilogue: column sums, fix-up, envelope accumulate, store --------------------------------
     DBG_T(40);
-
-    // ---- column sums of xs from the virtual all-ones row (all its output rows are equal) --------
-    if (lane < 16) red[wave * 16 + lane] = accv[0] * virt_scale;
-    __syncthreads();
     const float colsum = (red[n] + red[16 + n]) + (red[32 + n] + red[48 + n]);
-
-    // ---- fix-up, envelope accumulate, store ----------------------------------------------------
+    const _Float16* eoh = reinterpret_cast<const _Float16*>(eo);
+    float res[R];   // lane (kg, n < 4) ends up with the result of row 4*kg + n of tile r
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const bool tile_ok = (wave + 4 * r) < ntl;
-      const int rowb = (tile0 + trel[r]) * kTileRows + 4 * kg;
-      float ev[4];
+      const int trel = min(wave + 4 * r, u.ntl - 1);
+      float v[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int row = min(rowb + i, p.rows - 1);
-        ev[i] = (float)((g_f16_ptr)p.Eout)[(size_t)row * 16 + n];
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = rowb + i;
+        const float ev = (float)eoh[(trel * kTileRows + 4 * kg + i) * 16 + n];
         const float P = colsum - acc[r][0][i] * 33554432.f - acc[r][1][i] * 2097152.f;  // 2^25, 2^21
-        const float v = row16_sum(ev[i] * P);
-        if (tile_ok && n == 0 && row < p.rows) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, v);
+        v[i] = row16_sum(ev * P);
       }
+      const int sel = n & 3;
+      res[r] = sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3];
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int row = (u.tile0 + wave + 4 * r) * kTileRows + 4 * kg + n;
+      if ((wave + 4 * r) < u.ntl && n < 4 && row < u.p.rows)
+        store_from_float(u.p.out, (int64_t)u.b * u.p.out_ld + row, u.p.out_dt, res[r]);
     }
     DBG_T(41);
-    __syncthreads();  // red and the chunk buffers are reused by the next token
+    if (!has_next) break;
+    u = un;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int j = 0; j < kPrefetchBlocks; ++j) wq[r][j] = wnext[r][j];
   }
 }
 
-template <int R>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void stage_fast_kernel(const StageProb* __restrict__ probs, const WorkItem* __restrict__ items, StageProb single,
-                       int tiles_per_item) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u32x4* buf = reinterpret_cast<u32x4*>(smem);
-  float* red = reinterpret_cast<float*>(smem + 2 * kChunkVecs * 16);
-
-  // Blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of work items so that
-  // the items of one problem (which share Ein) meet in one L2.
-  const int nb = gridDim.x, bx = blockIdx.x;
-  const int xcd = bx & 7;
-  const int item = xcd * (nb >> 3) + min(xcd, nb & 7) + (bx >> 3);
-
-  StageProb p;
-  int tile0, ntl;
-  if (probs) {
-    const WorkItem it = items[item];
-    p = probs[it.prob];
-    tile0 = it.tile0;
-    ntl = it.ntiles;
-  } else {
-    p = single;
-    tile0 = item * tiles_per_item;
-    ntl = min(tiles_per_item, single.ntiles - tile0);
-  }
-  run_item<R>(p, tile0, ntl, buf, red);
-}
-
-template <int R>
-static int launch_r(const StageProb* probs_dev, const WorkItem* items_dev, int nblocks, int tiles_per_item,
-                    const StageProb* single, hipStream_t s) {
+template <int R, bool BATCH>
+static int launch_rb(const WorkItem* items_dev, int nitems, int tiles_per_item, const StageProb* single,
+                     hipStream_t s) {
   static bool attr_set = false;
+  static int max_wgs = 512;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_fast_kernel<R>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kFastSmemBytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_fast_kernel<R, BATCH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, fast_smem_bytes(R));
     if (e != hipSuccess) return (int)e;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      max_wgs = 2 * cus;   // two workgroups of four waves per compute unit
     attr_set = true;
   }
-  hipLaunchKernelGGL(stage_fast_kernel<R>, dim3((unsigned)nblocks), dim3(256), kFastSmemBytes, s, probs_dev,
-                     items_dev, *single, tiles_per_item);
+  const int nwg = nitems < max_wgs ? nitems : max_wgs;
+  hipLaunchKernelGGL((stage_fast_kernel<R, BATCH>), dim3((unsigned)nwg), dim3(256), fast_smem_bytes(R), s,
+                     items_dev, nitems, *single, tiles_per_item);
   return (int)hipGetLastError();
+}
+
+template <int R>
+static int launch_r(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
+                    const StageProb* single, hipStream_t s) {
+  if (probs_dev) return launch_rb<R, true>(items_dev, nitems, tiles_per_item, single, s);
+  return launch_rb<R, false>(items_dev, nitems, tiles_per_item, single, s);
 }
 
 #ifdef MDBF_DBG_TIMING
@@ -376,7 +544,7 @@ extern "C" int mdbf_dbg_read(void* host, size_t bytes) {
 #endif
 
 bool stage_is_fast(const StageProb& p) {
-  if (p.l != 16 || p.env_dt != MDBF_F16 || (p.K & 7) != 0) return false;
+  if (p.l != 16 || p.env_dt != MDBF_F16 || (p.K & 7) != 0 || p.KB < kPrefetchBlocks) return false;
   const int64_t row_bytes = p.vin_ld * (int64_t)dtype_size(p.vin_dt);
   return (row_bytes & 15) == 0;
 }
@@ -391,12 +559,11 @@ int mfma_tiles_per_item(long total_tiles) {
 
 int launch_stage_mfma(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
                       const StageProb* single, hipStream_t s) {
-  int nblocks = nitems;
-  if (!probs_dev) nblocks = (single->ntiles + tiles_per_item - 1) / tiles_per_item;
+  if (!probs_dev) nitems = (single->ntiles + tiles_per_item - 1) / tiles_per_item;
   switch (tiles_per_item) {
-    case 4: return launch_r<1>(probs_dev, items_dev, nblocks, tiles_per_item, single, s);
-    case 8: return launch_r<2>(probs_dev, items_dev, nblocks, tiles_per_item, single, s);
-    case 16: return launch_r<4>(probs_dev, items_dev, nblocks, tiles_per_item, single, s);
+    case 4: return launch_r<1>(probs_dev, items_dev, nitems, tiles_per_item, single, s);
+    case 8: return launch_r<2>(probs_dev, items_dev, nitems, tiles_per_item, single, s);
+    case 16: return launch_r<4>(probs_dev, items_dev, nitems, tiles_per_item, single, s);
     default: return (int)hipErrorInvalidValue;
   }
 }
