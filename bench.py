@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--copies", type=int, default=336, help="independent layers per step (336 x 3.17 MB > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the graph / hot / latency side measurements")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy, the known-size reference for the HBM traffic counters")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (--gpus 1); the forward product of one layer "
@@ -113,6 +115,13 @@ def main():
     mb.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+
+    if a.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.bitwise_xor(src, 85, out=dst)   # an elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     layers, Xs, Ys = make_device_layers(torch, mb, a.copies, seed=2)
     plan = mb.BatchPlan(layers, Xs, Ys)
@@ -142,8 +151,13 @@ def main():
     # ---- roofline of the dominant kernel (the stage kernel; two launches per step)
     launches = 2 * a.steps
     avg_launch_ms = ms_total / launches
-    roof = {"bound": "hbm", "kernel": "stage_mfma_kernel", "achieved": (bytes_step / 2) / avg_launch_ms / 1e6,
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None,
+    traffic = None   # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+    tpath = os.path.join(ROOT, "profiles", "traffic_attn_decode.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f)["hbm_bytes_per_layer_per_launch"] * a.copies
+    roof = {"bound": "hbm", "kernel": "stage_fast_kernel", "achieved": (bytes_step / 2) / avg_launch_ms / 1e6,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": traffic,
             "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_step / 2}
     roof["frac"] = roof["achieved"] / roof["peak"]
 

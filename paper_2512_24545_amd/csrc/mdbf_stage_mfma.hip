@@ -55,6 +55,10 @@ __device__ unsigned long long g_dbg_time[64 * 64];   // [block < 64][slot]
 
 constexpr int CB = 8;                      // 128-column blocks per LDS chunk
 constexpr int kChunkVecs = CB * 4 * 64;    // 16-byte vectors per chunk buffer (32 KB)
+#ifndef MDBF_LOAD_STEPS
+#define MDBF_LOAD_STEPS 1
+#endif
+constexpr int kLoadSteps = MDBF_LOAD_STEPS;   // the next chunk's loads are issued during this many block steps (1, 2 or 4)
 constexpr int kPrefetchBlocks = CB;        // sign words are loaded one chunk (8 blocks) ahead of their use
 __host__ __device__ constexpr int eo_vecs(int R) { return R * 4 * 16 * 2 < 256 ? 256 : R * 4 * 16 * 2; }  // Eout rows of a unit, 16 B each, a multiple of the 256 threads
 __host__ __device__ constexpr int fast_smem_bytes(int R) { return 2 * kChunkVecs * 16 + eo_vecs(R) * 16 + 4 * 16 * 4; }
@@ -122,6 +126,9 @@ __device__ __forceinline__ void stage_addr(const void* ein, int ch, const void* 
 }
 
 __device__ __forceinline__ void stage_load_part(const StageAddr& sa, int part, StageRegs& sr) {
+#ifdef MDBF_DBG_NOSTAGELOAD
+  return;
+#endif
   sr.e[2 * part] = sa.ep[4 * part];
   sr.e[2 * part + 1] = sa.ep[4 * part + 2];
   if (part == 0) {
@@ -387,17 +394,18 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
       const u32x4* bufc = buf + par * kChunkVecs;
 #pragma unroll
       for (int jj = 0; jj < CB; ++jj) {
-        if (jj < 4) {
-          // a quarter of the next chunk's loads per step: they are all at least four steps old when
-          // the chunk ends, and they do not arrive at the memory pipeline in one burst
+        if (jj < kLoadSteps) {
+          // a share of the next chunk's loads per step: they are all several steps old when the chunk
+          // ends, and they do not arrive at the memory pipeline in one burst
 #pragma unroll
-          for (int j = 2 * jj; j < 2 * jj + 2; ++j) {
+          for (int j = (CB / kLoadSteps) * jj; j < (CB / kLoadSteps) * (jj + 1); ++j) {
             const int qn = (c + 1) * CB + j;
             const uint64_t off = (qn < KB) ? (uint64_t)qn * 256u : 0u;
 #pragma unroll
             for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)((uint64_t)u.sbase[r] + off))[lane];
           }
-          stage_load_part(sa, jj, sr);
+#pragma unroll
+          for (int part = (4 / kLoadSteps) * jj; part < (4 / kLoadSteps) * (jj + 1); ++part) stage_load_part(sa, part, sr);
         }
         uint32_t word[R];
 #pragma unroll
@@ -446,12 +454,13 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
       const u32x4* bufc = buf + par * kChunkVecs;
 #pragma unroll
       for (int jj = 0; jj < CB; ++jj) {
-        if (jj < 4) {
+        if (jj < kLoadSteps) {
 #pragma unroll
-          for (int j = 2 * jj; j < 2 * jj + 2; ++j)
+          for (int j = (CB / kLoadSteps) * jj; j < (CB / kLoadSteps) * (jj + 1); ++j)
 #pragma unroll
             for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)(un.sbase[r] + j * 64))[lane];
-          stage_load_part(sa, jj, sr);
+#pragma unroll
+          for (int part = (4 / kLoadSteps) * jj; part < (4 / kLoadSteps) * (jj + 1); ++part) stage_load_part(sa, part, sr);
         }
         if (c * CB + jj < KB) {
           uint32_t word[R];
