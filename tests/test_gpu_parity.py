@@ -202,3 +202,49 @@ def test_batch_fast_layers_equal_single_calls(gpu):
     for Yb, Y1, ref in zip(Ys, singles, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
         assert torch.equal(Yb, Y1)
+
+
+# ---------------------------------------------------------------- prefill-shaped batch of tokens
+@pytest.mark.parametrize("x_dtype", ["f16", "bf16"])
+def test_prefill_tokens_sampled_against_oracle(gpu, x_dtype):
+    """4096x4096, k=2656, l=16, 2048 tokens, envelopes |N|+0.1 (outputs reach 1e6: fp32 Y).
+    All 2048 rows are computed on the GPU; 6 sampled tokens are checked against the oracle."""
+    torch, mb = gpu
+    L, X = synth.config_prefill(T=2048, x_dtype=x_dtype)
+    dl = mb.DeviceLayer.from_host(L)
+    Xd = _to_dev(torch, X, x_dtype)
+    Y = mb.mdbf_forward(dl, Xd, y_dtype="f32")
+    torch.cuda.synchronize()
+    Yh = Y.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(Yh))
+    rows = [0, 1, 777, 1024, 2046, 2047]
+    ref = orc.forward_factored(*_oracle_args(L), X[rows])
+    assert orc.max_rel_error(Yh[rows], ref) <= TOL
+    # every token is an independent product: rows must not leak into each other
+    Y1 = mb.mdbf_forward(dl, Xd[777:778].contiguous(), y_dtype="f32")
+    torch.cuda.synchronize()
+    assert torch.equal(Y1[0], Y[777])
+
+
+# ---------------------------------------------------------------- the synthetic decoder stack
+@pytest.mark.parametrize("budget", ["1.0", "1.5", "2.0"])
+@pytest.mark.parametrize("T", [1, 8])
+def test_decoder_stack_layer_through_batch(gpu, budget, T):
+    """One layer of the 32-layer stack (q,k,v,o,gate,up,down: 7 independent products) per budget,
+    issued as one plan; each matrix is compared with the oracle."""
+    torch, mb = gpu
+    layer_idx = {"1.0": 0, "1.5": 15, "2.0": 31}[budget]
+    layers, Xs, Ys, refs = [], [], [], []
+    for mat in range(7):
+        L, X = synth.stack_matrix(budget, layer_idx, mat, T=T)
+        layers.append(mb.DeviceLayer.from_host(L))
+        Xs.append(_to_dev(torch, X, "f16"))
+        Ys.append(torch.zeros((T, L["m"]), dtype=torch.float32, device="cuda:0"))
+        refs.append(orc.forward_factored(*_oracle_args(L), X))
+        sp = synth.stack_matrix_spec(budget, layer_idx, mat)
+        assert abs(mb.mdbf_bpw(sp["m"], sp["n"], sp["k"], sp["l"]) - float(budget)) < 0.01
+    plan = mb.BatchPlan(layers, Xs, Ys)
+    plan.run()
+    torch.cuda.synchronize()
+    for Yb, ref in zip(Ys, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
