@@ -35,6 +35,15 @@ int check_desc(const mdbf_desc_t* d) {
 
 size_t z_bytes(const mdbf_desc_t* d, int T) { return align_up((size_t)T * (size_t)kpad_of(d->k) * 4u, 256); }
 
+// Buffers for the pre-scaled activations of the two stages (only for small token counts and the
+// l = 16 / fp16-envelope case the matrix-core kernel serves; zero otherwise).
+bool wants_xs(const mdbf_desc_t* d, int T) {
+  return T <= kMaxPreTokens && d->l == 16 && d->env_dtype == MDBF_F16 && !(d->flags & MDBF_FLAG_PRECISE);
+}
+size_t xs1_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? align_up(xs_bytes_for(d->n, T), 256) : 0; }
+size_t xs2_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? align_up(xs_bytes_for(d->k, T), 256) : 0; }
+size_t layer_ws_bytes(const mdbf_desc_t* d, int T) { return z_bytes(d, T) + xs1_bytes(d, T) + xs2_bytes(d, T); }
+
 int check_layer(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
                 int64_t ldx, void* Y, int64_t ldy, int T) {
   int st = check_desc(d);
@@ -51,7 +60,10 @@ int check_layer(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf
 
 // the two stage problems of one layer (paper Eq. "me-dbf-expand": V first, then U)
 void make_stages(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
-                 int64_t ldx, void* Y, int64_t ldy, int T, void* z, StageProb out[2]) {
+                 int64_t ldx, void* Y, int64_t ldy, int T, void* ws, StageProb out[2]) {
+  void* z = ws;
+  unsigned char* xs1 = (unsigned char*)ws + z_bytes(d, T);
+  unsigned char* xs2 = xs1 + xs1_bytes(d, T);
   StageProb s1;
   memset(&s1, 0, sizeof(s1));
   s1.S = (const uint32_t*)SB;
@@ -59,6 +71,7 @@ void make_stages(const mdbf_desc_t* d, const void* SA, const void* SB, const mdb
   s1.Eout = env->G_dev;
   s1.vin = X;
   s1.out = z;
+  s1.xs = xs1_bytes(d, T) ? xs1 : nullptr;
   s1.vin_ld = ldx;
   s1.out_ld = kpad_of(d->k);
   s1.rows = d->k;
@@ -77,6 +90,7 @@ void make_stages(const mdbf_desc_t* d, const void* SA, const void* SB, const mdb
   s2.Eout = env->A_dev;
   s2.vin = z;
   s2.out = Y;
+  s2.xs = xs2_bytes(d, T) ? xs2 : nullptr;
   s2.vin_ld = kpad_of(d->k);
   s2.out_ld = ldy;
   s2.rows = d->m;
@@ -142,7 +156,7 @@ int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out) {
   int st = check_desc(desc);
   if (st) return st;
   if (!bytes_out || T < 1) return MDBF_EINVAL;
-  *bytes_out = z_bytes(desc, T);
+  *bytes_out = layer_ws_bytes(desc, T);
   return MDBF_OK;
 }
 
@@ -153,7 +167,7 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
   if (st) return st;
   if (!workspace_dev) return MDBF_EINVAL;
   if (!aligned16(workspace_dev)) return MDBF_EALIGN;
-  if (workspace_bytes < z_bytes(desc, T)) return MDBF_EWORKSPACE;
+  if (workspace_bytes < layer_ws_bytes(desc, T)) return MDBF_EWORKSPACE;
   StageProb sp[2];
   make_stages(desc, SA_packed_dev, SB_packed_dev, env, X_dev, ldx, Y_dev, ldy, T, workspace_dev, sp);
   hipStream_t s = (hipStream_t)stream;
@@ -161,8 +175,15 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
     int e;
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
-    else if (stage_is_fast(sp[i]))
-      e = launch_stage_mfma(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], s);
+    else if (stage_is_fast(sp[i])) {
+      const bool pre = sp[i].xs != nullptr;
+      if (pre) {
+        const int units = T * ((sp[i].KB + 7) / 8);
+        e = launch_scale_in(nullptr, 1, units, &sp[i], s);
+        if (e) return hip_fail(e);
+      }
+      e = launch_stage_mfma(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], pre, s);
+    }
     else
       e = launch_stage_generic(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], s);
     if (e) return hip_fail(e);
@@ -183,7 +204,7 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
     precise += (L->desc.flags & MDBF_FLAG_PRECISE) ? 1 : 0;
     tiles[0] += num_tiles(L->desc.k);
     tiles[1] += num_tiles(L->desc.m);
-    ws += z_bytes(&L->desc, L->T);
+    ws += layer_ws_bytes(&L->desc, L->T);
   }
   if (precise != 0 && precise != count) return MDBF_EUNSUPPORTED;  // all or none
   memset(h, 0, sizeof(*h));
@@ -244,16 +265,21 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   size_t zoff = 0;
   int ni[2] = {0, 0};
   int fast[2] = {1, 1};
+  int pre[2] = {1, 1};
+  int max_units[2] = {1, 1};
   const int tpi = h.tiles_per_item;
   for (int i = 0; i < count; ++i) {
     const mdbf_layer_t* L = &layers[i];
     StageProb sp[2];
     make_stages(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev, L->ldy, L->T,
                 (unsigned char*)workspace_dev + zoff, sp);
-    zoff += z_bytes(&L->desc, L->T);
+    zoff += layer_ws_bytes(&L->desc, L->T);
     for (int s = 0; s < 2; ++s) {
       probs[s][i] = sp[s];
       if (!stage_is_fast(sp[s])) fast[s] = 0;
+      if (!sp[s].xs) pre[s] = 0;
+      const int units = sp[s].T * ((sp[s].KB + 7) / 8);
+      if (units > max_units[s]) max_units[s] = units;
       for (int t0 = 0; t0 < sp[s].ntiles; t0 += tpi) {
         WorkItem w;
         memset(&w, 0, sizeof(w));
@@ -268,6 +294,10 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   }
   h.fast[0] = fast[0];
   h.fast[1] = fast[1];
+  h.pre[0] = fast[0] && pre[0];
+  h.pre[1] = fast[1] && pre[1];
+  h.max_units[0] = max_units[0];
+  h.max_units[1] = max_units[1];
   memcpy(base, &h, sizeof(h));
   return MDBF_OK;
 }
@@ -290,8 +320,13 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
     int e;
     if (h.precise)
       e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
-    else if (h.fast[st])
-      e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
+    else if (h.fast[st]) {
+      if (h.pre[st]) {
+        e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);
+        if (e) return hip_fail(e);
+      }
+      e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item, &dummy, h.pre[st] != 0, s);
+    }
     else
       e = launch_stage_generic(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
     if (e) return hip_fail(e);

@@ -52,6 +52,7 @@ struct StageProb {
   const void* Eout;
   const void* vin;
   void* out;
+  void* xs;            // pre-scaled activations in B-operand order (T x chunks x 32 KB), or null
   int64_t vin_ld, out_ld;
   int32_t rows, K, l, T;
   int32_t KB, ntiles;
@@ -65,7 +66,7 @@ struct alignas(128) WorkItem {
   StageProb p;
   int32_t tile0, ntiles, prob, pad_;
 };
-static_assert(sizeof(StageProb) == 96, "StageProb layout is read dword by dword on the device");
+static_assert(sizeof(StageProb) == 104, "StageProb layout is read dword by dword on the device");
 static_assert(sizeof(WorkItem) == 128, "WorkItem must be 128 bytes");
 
 // Plan of a batched forward (host and device copies are byte-identical).
@@ -76,7 +77,8 @@ struct PlanHeader {
   int32_t tiles_per_item;     // upper bound of WorkItem::ntiles
   int32_t precise;            // all layers use the fp32 path
   int32_t fast[2];            // every problem of the stage qualifies for the fast matrix-core variant
-  int32_t pad_[2];
+  int32_t pre[2];             // ... and has a buffer for pre-scaled activations (written by the scale-in kernel)
+  int32_t max_units[2];       // largest tokens x chunks of a problem of the stage (grid of the scale-in kernel)
   uint64_t probs_off[2];      // byte offsets of StageProb[count] for stage 1 / 2
   uint64_t items_off[2];      // byte offsets of WorkItem[nitems[s]]
   uint64_t total_bytes;
@@ -88,10 +90,17 @@ int launch_pack(const int8_t* signs, int rows, int cols, int64_t ld, uint32_t* p
 int launch_unpack(const uint32_t* packed, int rows, int cols, int8_t* signs, int64_t ld, hipStream_t s);
 int launch_stage_precise(const StageProb* probs_dev, const WorkItem* items_dev, int nitems,
                          const StageProb* single, hipStream_t s);
+// pre: the problems' xs buffers hold the pre-scaled activations (launch_scale_in ran before)
 int launch_stage_mfma(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
-                      const StageProb* single, hipStream_t s);
+                      const StageProb* single, bool pre, hipStream_t s);
 int launch_stage_generic(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
                          const StageProb* single, hipStream_t s);
+// scale-in kernel: writes xs = fp16(Ein * vin) of every (problem, token, 1024-column chunk) to p.xs in the
+// order the matrix-core kernel copies it to LDS (paper Eq. "me-dbf-expand", the D_b / D_q factors)
+int launch_scale_in(const StageProb* probs_dev, int count, int max_units, const StageProb* single, hipStream_t s);
+// bytes of one problem's xs buffer
+size_t xs_bytes_for(int K, int T);
+constexpr int kMaxPreTokens = 16;   // token counts up to this use the scale-in kernel
 // true if the fast matrix-core variant can run the problem (l == 16, fp16 envelopes, K % 8 == 0,
 // 16-byte aligned activation rows); otherwise the general variant is used
 bool stage_is_fast(const StageProb& p);

@@ -186,6 +186,47 @@ __device__ __forceinline__ void stage_store(const StageRegs& sr, int vin_dt, u32
   }
 }
 
+// How a workgroup gets the scaled activations of a chunk into LDS.
+//  PRE = false: computes them itself from Ein and vin (stage_addr / stage_load_part / stage_store).
+//  PRE = true : the scale-in kernel has written them, in LDS order, to the problem's xs buffer; the
+//               workgroup copies 32 KB per chunk (8 vectors per thread), no arithmetic.
+template <bool PRE>
+struct Stager;
+
+template <>
+struct Stager<false> {
+  StageRegs sr;
+  StageAddr sa;
+  int vin_dt;
+  __device__ __forceinline__ void addr(const void* ein, const void* vin_row, int dt, const u32x4* /*xs_tok*/, int chunk,
+                                       int K, int ch, int st_col, int /*tid*/) {
+    vin_dt = dt;
+    stage_addr(ein, ch, vin_row, dt, chunk * (CB * kBlockCols) + st_col, K, sr, sa);
+  }
+  __device__ __forceinline__ void load_part(int part) { stage_load_part(sa, part, sr); }
+  __device__ __forceinline__ void store(u32x4* bufbase, int st_vec, int st_sw, int /*tid*/) {
+    stage_store(sr, vin_dt, bufbase + st_vec, st_sw);
+  }
+};
+
+template <>
+struct Stager<true> {
+  u32x4 cp[8];
+  g_u32x4_ptr src;
+  __device__ __forceinline__ void addr(const void*, const void*, int, const u32x4* xs_tok, int chunk, int, int, int,
+                                       int tid) {
+    src = (g_u32x4_ptr)xs_tok + ((size_t)chunk * kChunkVecs + tid);
+  }
+  __device__ __forceinline__ void load_part(int part) {
+    cp[2 * part] = src[(2 * part) * 256];
+    cp[2 * part + 1] = src[(2 * part + 1) * 256];
+  }
+  __device__ __forceinline__ void store(u32x4* bufbase, int, int, int tid) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bufbase[tid + 256 * i] = cp[i];
+  }
+};
+
 // B operands of one block: the four MFMA steps plus this wave's share of the virtual row.
 struct BlockOps {
   u32x4 v[5];
@@ -236,6 +277,7 @@ struct Unit {
   int tile0, ntl, b, item;
   const uint32_t* sbase[R];
   const void* vin_row;
+  const u32x4* xs_tok;   // pre-scaled activations of the unit's token (all chunks), or null
 };
 
 template <int R>
@@ -248,6 +290,8 @@ __device__ __forceinline__ void finish_unit(Unit<R>& u, int wave) {
     u.sbase[r] = u.p.S + (size_t)(u.tile0 + trel) * (size_t)(u.p.KB * 64);
   }
   u.vin_row = (const char*)u.p.vin + (size_t)u.b * (size_t)u.p.vin_ld * (size_t)dtype_size(u.p.vin_dt);
+  const int nch = (u.p.KB + CB - 1) / CB;
+  u.xs_tok = (const u32x4*)u.p.xs + (size_t)u.b * (size_t)nch * (size_t)kChunkVecs;
 }
 
 // In batch mode the 128-byte work item is fetched one dword per lane and broadcast to scalar registers
@@ -260,29 +304,30 @@ template <int R, bool BATCH>
 __device__ __forceinline__ void make_unit(uint32_t desc, const StageProb& single, int tiles_per_item, int item,
                                           int wave, Unit<R>& u) {
   if (BATCH) {
-    uint32_t d[26];
+    uint32_t d[28];
 #pragma unroll
-    for (int i = 0; i < 26; ++i) d[i] = __builtin_amdgcn_readlane(desc, i);
+    for (int i = 0; i < 28; ++i) d[i] = __builtin_amdgcn_readlane(desc, i);
     auto ptr = [&](int i) { return (uint64_t)d[i] | ((uint64_t)d[i + 1] << 32); };
     u.p.S = (const uint32_t*)ptr(0);
     u.p.Ein = (const void*)ptr(2);
     u.p.Eout = (const void*)ptr(4);
     u.p.vin = (const void*)ptr(6);
     u.p.out = (void*)ptr(8);
-    u.p.vin_ld = (int64_t)ptr(10);
-    u.p.out_ld = (int64_t)ptr(12);
-    u.p.rows = (int)d[14];
-    u.p.K = (int)d[15];
-    u.p.l = (int)d[16];
-    u.p.T = (int)d[17];
-    u.p.KB = (int)d[18];
-    u.p.ntiles = (int)d[19];
-    u.p.env_dt = (int)d[20];
-    u.p.vin_dt = (int)d[21];
-    u.p.out_dt = (int)d[22];
+    u.p.xs = (void*)ptr(10);
+    u.p.vin_ld = (int64_t)ptr(12);
+    u.p.out_ld = (int64_t)ptr(14);
+    u.p.rows = (int)d[16];
+    u.p.K = (int)d[17];
+    u.p.l = (int)d[18];
+    u.p.T = (int)d[19];
+    u.p.KB = (int)d[20];
+    u.p.ntiles = (int)d[21];
+    u.p.env_dt = (int)d[22];
+    u.p.vin_dt = (int)d[23];
+    u.p.out_dt = (int)d[24];
     u.p.pad_ = 0;
-    u.tile0 = (int)d[24];
-    u.ntl = (int)d[25];
+    u.tile0 = (int)d[26];
+    u.ntl = (int)d[27];
   } else {
     u.p = single;
     u.tile0 = item * tiles_per_item;
@@ -293,7 +338,7 @@ __device__ __forceinline__ void make_unit(uint32_t desc, const StageProb& single
   finish_unit<R>(u, wave);
 }
 
-template <int R, bool BATCH>
+template <int R, bool BATCH, bool PRE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single, int tiles_per_item) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -351,10 +396,12 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
 #pragma unroll
     for (int j = 0; j < kPrefetchBlocks; ++j)
       wq[r][j] = ((g_u32_ptr)(u.sbase[r] + j * 64))[lane];   // KB >= 8 for every fast problem
-  StageRegs sr;
-  stage_load(u.p.Ein, ch, u.vin_row, u.p.vin_dt, st_col, u.p.K, sr);
+  Stager<PRE> stg;
+  stg.addr(u.p.Ein, u.vin_row, u.p.vin_dt, u.xs_tok, 0, u.p.K, ch, st_col, tid);
+#pragma unroll
+  for (int part = 0; part < 4; ++part) stg.load_part(part);
   int par = 0;
-  stage_store(sr, u.p.vin_dt, buf + st_vec, st_sw);
+  stg.store(buf, st_vec, st_sw, tid);
   __syncthreads();
 
   DBG_UNIT_DECL;
@@ -388,8 +435,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
     uint32_t wnext[R][kPrefetchBlocks];
 #pragma unroll 1
     for (int c = 0; c < nchunks - 1; ++c) {
-      StageAddr sa;
-      stage_addr(u.p.Ein, ch, u.vin_row, u.p.vin_dt, (c + 1) * (CB * kBlockCols) + st_col, u.p.K, sr, sa);
+      stg.addr(u.p.Ein, u.vin_row, u.p.vin_dt, u.xs_tok, c + 1, u.p.K, ch, st_col, tid);
       DBG_T(1 + 4 * c);
       const u32x4* bufc = buf + par * kChunkVecs;
 #pragma unroll
@@ -405,7 +451,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
             for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)((uint64_t)u.sbase[r] + off))[lane];
           }
 #pragma unroll
-          for (int part = (4 / kLoadSteps) * jj; part < (4 / kLoadSteps) * (jj + 1); ++part) stage_load_part(sa, part, sr);
+          for (int part = (4 / kLoadSteps) * jj; part < (4 / kLoadSteps) * (jj + 1); ++part) stg.load_part(part);
         }
         uint32_t word[R];
 #pragma unroll
@@ -416,7 +462,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
       }
       DBG_T(2 + 4 * c);
 #ifndef MDBF_DBG_NOSTAGE
-      stage_store(sr, u.p.vin_dt, buf + (par ^ 1) * kChunkVecs + st_vec, st_sw);
+      stg.store(buf + (par ^ 1) * kChunkVecs, st_vec, st_sw, tid);
 #endif
       DBG_T(3 + 4 * c);
       __syncthreads();
@@ -441,8 +487,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
       } else if (has_next) {
         make_unit<R, BATCH>(desc_next, single, tiles_per_item, ni, wave, un);
       }
-      StageAddr sa;
-      stage_addr(un.p.Ein, ch, un.vin_row, un.p.vin_dt, st_col, un.p.K, sr, sa);
+      stg.addr(un.p.Ein, un.vin_row, un.p.vin_dt, un.xs_tok, 0, un.p.K, ch, st_col, tid);
       u32x4 eoreg[eo_vecs(R) / 256];
 #pragma unroll
       for (int t = 0; t < eo_vecs(R) / 256; ++t) {
@@ -460,7 +505,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
 #pragma unroll
             for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)(un.sbase[r] + j * 64))[lane];
 #pragma unroll
-          for (int part = (4 / kLoadSteps) * jj; part < (4 / kLoadSteps) * (jj + 1); ++part) stage_load_part(sa, part, sr);
+          for (int part = (4 / kLoadSteps) * jj; part < (4 / kLoadSteps) * (jj + 1); ++part) stg.load_part(part);
         }
         if (c * CB + jj < KB) {
           uint32_t word[R];
@@ -476,7 +521,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
 #pragma unroll
       for (int t = 0; t < eo_vecs(R) / 256; ++t) eo[tid + 256 * t] = eoreg[t];
 #ifndef MDBF_DBG_NOSTAGE
-      stage_store(sr, un.p.vin_dt, buf + (par ^ 1) * kChunkVecs + st_vec, st_sw);
+      stg.store(buf + (par ^ 1) * kChunkVecs, st_vec, st_sw, tid);
 #endif
       DBG_T(3 + 4 * c);
       __syncthreads();
@@ -518,13 +563,13 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
   }
 }
 
-template <int R, bool BATCH>
-static int launch_rb(const WorkItem* items_dev, int nitems, int tiles_per_item, const StageProb* single,
-                     hipStream_t s) {
+template <int R, bool BATCH, bool PRE>
+static int launch_rbp(const WorkItem* items_dev, int nitems, int tiles_per_item, const StageProb* single,
+                      hipStream_t s) {
   static bool attr_set = false;
   static int max_wgs = 512;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_fast_kernel<R, BATCH>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_fast_kernel<R, BATCH, PRE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, fast_smem_bytes(R));
     if (e != hipSuccess) return (int)e;
     int dev = 0, cus = 0;
@@ -534,16 +579,52 @@ static int launch_rb(const WorkItem* items_dev, int nitems, int tiles_per_item, 
     attr_set = true;
   }
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
-  hipLaunchKernelGGL((stage_fast_kernel<R, BATCH>), dim3((unsigned)nwg), dim3(256), fast_smem_bytes(R), s,
+  hipLaunchKernelGGL((stage_fast_kernel<R, BATCH, PRE>), dim3((unsigned)nwg), dim3(256), fast_smem_bytes(R), s,
                      items_dev, nitems, *single, tiles_per_item);
   return (int)hipGetLastError();
 }
 
 template <int R>
 static int launch_r(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
-                    const StageProb* single, hipStream_t s) {
-  if (probs_dev) return launch_rb<R, true>(items_dev, nitems, tiles_per_item, single, s);
-  return launch_rb<R, false>(items_dev, nitems, tiles_per_item, single, s);
+                    const StageProb* single, bool pre, hipStream_t s) {
+  if (probs_dev) {
+    if (pre) return launch_rbp<R, true, true>(items_dev, nitems, tiles_per_item, single, s);
+    return launch_rbp<R, true, false>(items_dev, nitems, tiles_per_item, single, s);
+  }
+  if (pre) return launch_rbp<R, false, true>(items_dev, nitems, tiles_per_item, single, s);
+  return launch_rbp<R, false, false>(items_dev, nitems, tiles_per_item, single, s);
+}
+
+// ---- scale-in kernel: one workgroup per (problem, token, chunk) -------------------------------------
+__global__ __launch_bounds__(256) void scale_in_kernel(const StageProb* __restrict__ probs, StageProb single) {
+  StageProb p;
+  if (probs) p = probs[blockIdx.y];
+  else p = single;
+  const int nch = (p.KB + CB - 1) / CB;
+  const int unit = blockIdx.x;
+  if (unit >= nch * p.T) return;
+  const int b = unit / nch, c = unit - b * nch;
+  const int tid = threadIdx.x;
+  const int ch = tid & 1, oo = tid >> 1;
+  const int st_q = oo >> 4, st_f = (oo & 15) >> 2, st_kg = oo & 3;
+  const int st_col = st_q * kBlockCols + st_f * 32 + st_kg * 8;
+  const int st_vec = (st_q * 4 + st_f) * 64 + st_kg * 16 + ch * 8;
+  const int st_sw = (st_kg + 4 * (st_f & 1)) & 7;
+  const void* vin_row = (const char*)p.vin + (size_t)b * (size_t)p.vin_ld * (size_t)dtype_size(p.vin_dt);
+  StageRegs sr;
+  stage_load(p.Ein, ch, vin_row, p.vin_dt, c * (CB * kBlockCols) + st_col, p.K, sr);
+  u32x4* dst = (u32x4*)p.xs + ((size_t)b * nch + c) * (size_t)kChunkVecs + st_vec;
+  stage_store(sr, p.vin_dt, dst, st_sw);
+}
+
+int launch_scale_in(const StageProb* probs_dev, int count, int max_units, const StageProb* single, hipStream_t s) {
+  hipLaunchKernelGGL(scale_in_kernel, dim3((unsigned)max_units, (unsigned)count), dim3(256), 0, s, probs_dev, *single);
+  return (int)hipGetLastError();
+}
+
+size_t xs_bytes_for(int K, int T) {
+  const int nch = (num_blocks(K) + CB - 1) / CB;
+  return (size_t)T * (size_t)nch * (size_t)kChunkVecs * 16u;
 }
 
 #ifdef MDBF_DBG_TIMING
@@ -567,12 +648,12 @@ int mfma_tiles_per_item(long total_tiles) {
 }
 
 int launch_stage_mfma(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
-                      const StageProb* single, hipStream_t s) {
+                      const StageProb* single, bool pre, hipStream_t s) {
   if (!probs_dev) nitems = (single->ntiles + tiles_per_item - 1) / tiles_per_item;
   switch (tiles_per_item) {
-    case 4: return launch_r<1>(probs_dev, items_dev, nitems, tiles_per_item, single, s);
-    case 8: return launch_r<2>(probs_dev, items_dev, nitems, tiles_per_item, single, s);
-    case 16: return launch_r<4>(probs_dev, items_dev, nitems, tiles_per_item, single, s);
+    case 4: return launch_r<1>(probs_dev, items_dev, nitems, tiles_per_item, single, pre, s);
+    case 8: return launch_r<2>(probs_dev, items_dev, nitems, tiles_per_item, single, pre, s);
+    case 16: return launch_r<4>(probs_dev, items_dev, nitems, tiles_per_item, single, pre, s);
     default: return (int)hipErrorInvalidValue;
   }
 }
