@@ -1,6 +1,7 @@
 // C ABI of libmdbf: argument validation, storage accounting, plans and kernel dispatch.
 // Every argument check happens before the first HIP call.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -40,8 +41,23 @@ size_t z_bytes(const mdbf_desc_t* d, int T) { return align_up((size_t)T * (size_
 bool wants_xs(const mdbf_desc_t* d, int T) {
   return T <= kMaxPreTokens && d->l == 16 && d->env_dtype == MDBF_F16 && !(d->flags & MDBF_FLAG_PRECISE);
 }
-size_t xs1_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? align_up(xs_bytes_for(d->n, T), 256) : 0; }
-size_t xs2_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? align_up(xs_bytes_for(d->k, T), 256) : 0; }
+size_t xs_need(int K, int T) {
+  const size_t a = xs_bytes_for(K, T), b = xs_bytes_for_mx(K, T);
+  return align_up(a > b ? a : b, 256);
+}
+size_t xs1_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? xs_need(d->n, T) : 0; }
+size_t xs2_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? xs_need(d->k, T) : 0; }
+
+// The block-scaled variant is the default where it applies; MDBF_DISABLE_MX=1 in the environment selects
+// the fp16 variant instead (read once).
+bool mx_enabled() {
+  static const bool on = [] {
+    const char* e = getenv("MDBF_DISABLE_MX");
+    return !(e && e[0] && e[0] != '0');
+  }();
+  return on;
+}
+bool use_mx(const StageProb& p) { return mx_enabled() && stage_is_fast(p) && stage_is_mx(p); }
 size_t layer_ws_bytes(const mdbf_desc_t* d, int T) { return z_bytes(d, T) + xs1_bytes(d, T) + xs2_bytes(d, T); }
 
 int check_layer(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
@@ -175,6 +191,11 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
     int e;
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
+    else if (use_mx(sp[i])) {
+      e = launch_scale_in_mx(nullptr, 1, T * mx_chunks(sp[i].KB), &sp[i], s);
+      if (e) return hip_fail(e);
+      e = launch_stage_mx(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], s);
+    }
     else if (stage_is_fast(sp[i])) {
       const bool pre = sp[i].xs != nullptr;
       if (pre) {
@@ -267,6 +288,8 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   int fast[2] = {1, 1};
   int pre[2] = {1, 1};
   int max_units[2] = {1, 1};
+  int mx[2] = {1, 1};
+  int max_units_mx[2] = {1, 1};
   const int tpi = h.tiles_per_item;
   for (int i = 0; i < count; ++i) {
     const mdbf_layer_t* L = &layers[i];
@@ -280,6 +303,9 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
       if (!sp[s].xs) pre[s] = 0;
       const int units = sp[s].T * ((sp[s].KB + 7) / 8);
       if (units > max_units[s]) max_units[s] = units;
+      if (!use_mx(sp[s])) mx[s] = 0;
+      const int units_mx = sp[s].T * mx_chunks(sp[s].KB);
+      if (units_mx > max_units_mx[s]) max_units_mx[s] = units_mx;
       for (int t0 = 0; t0 < sp[s].ntiles; t0 += tpi) {
         WorkItem w;
         memset(&w, 0, sizeof(w));
@@ -298,6 +324,10 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   h.pre[1] = fast[1] && pre[1];
   h.max_units[0] = max_units[0];
   h.max_units[1] = max_units[1];
+  for (int s = 0; s < 2; ++s) {
+    h.mx[s] = mx[s];
+    h.max_units_mx[s] = max_units_mx[s];
+  }
   memcpy(base, &h, sizeof(h));
   return MDBF_OK;
 }
@@ -320,6 +350,11 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
     int e;
     if (h.precise)
       e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
+    else if (h.mx[st]) {
+      e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
+      if (e) return hip_fail(e);
+      e = launch_stage_mx(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
+    }
     else if (h.fast[st]) {
       if (h.pre[st]) {
         e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);

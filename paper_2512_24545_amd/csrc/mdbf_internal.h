@@ -79,6 +79,8 @@ struct PlanHeader {
   int32_t fast[2];            // every problem of the stage qualifies for the fast matrix-core variant
   int32_t pre[2];             // ... and has a buffer for pre-scaled activations (written by the scale-in kernel)
   int32_t max_units[2];       // largest tokens x chunks of a problem of the stage (grid of the scale-in kernel)
+  int32_t mx[2];              // every problem of the stage qualifies for the block-scaled variant
+  int32_t max_units_mx[2];    // grid of that variant's scale-in kernel
   uint64_t probs_off[2];      // byte offsets of StageProb[count] for stage 1 / 2
   uint64_t items_off[2];      // byte offsets of WorkItem[nitems[s]]
   uint64_t total_bytes;
@@ -100,6 +102,15 @@ int launch_stage_generic(const StageProb* probs_dev, const WorkItem* items_dev, 
 int launch_scale_in(const StageProb* probs_dev, int count, int max_units, const StageProb* single, hipStream_t s);
 // bytes of one problem's xs buffer
 size_t xs_bytes_for(int K, int T);
+// Block-scaled (MX) variant of the matrix-core kernel: signs as fp4, activations as three fp6 limbs with a
+// power-of-two scale per 32 values, written by its own scale-in kernel into the same xs buffer.
+size_t xs_bytes_for_mx(int K, int T);
+int mx_chunks(int KB);                       // chunks of one token's activation stream
+bool stage_is_mx(const StageProb& p);        // on top of stage_is_fast
+int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single,
+                       hipStream_t s);
+int launch_stage_mx(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
+                    const StageProb* single, hipStream_t s);
 constexpr int kMaxPreTokens = 16;   // token counts up to this use the scale-in kernel
 // true if the fast matrix-core variant can run the problem (l == 16, fp16 envelopes, K % 8 == 0,
 // 16-byte aligned activation rows); otherwise the general variant is used

@@ -555,6 +555,8 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
     }
     DBG_T(41);
     if (!has_next) break;
+    // a one-chunk unit writes red / eo again before any other barrier: wait for the slowest reader
+    if (nchunks == 1) __syncthreads();
     u = un;
 #pragma unroll
     for (int r = 0; r < R; ++r)

@@ -190,8 +190,8 @@ def test_batch_mixed_layers(gpu):
     for Yb, Y1, ref in zip(Ys, singles, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
         assert orc.max_rel_error(Y1.cpu().numpy(), ref) <= TOL
-        # the two kernel variants round the staged activations slightly differently
-        assert orc.max_rel_error(Yb.cpu().numpy(), Y1.cpu().numpy().astype(np.float64)) <= 1e-4
+        # the kernel variants quantise the staged activations differently (fp16 vs three fp6 limbs)
+        assert orc.max_rel_error(Yb.cpu().numpy(), Y1.cpu().numpy().astype(np.float64)) <= 5e-4
 
 
 def test_batch_fast_layers_equal_single_calls(gpu):
@@ -221,9 +221,13 @@ def test_prefill_tokens_sampled_against_oracle(gpu, x_dtype):
     ref = orc.forward_factored(*_oracle_args(L), X[rows])
     assert orc.max_rel_error(Yh[rows], ref) <= TOL
     # every token is an independent product: rows must not leak into each other
+    Ysub = mb.mdbf_forward(dl, Xd[760:800].contiguous(), y_dtype="f32")
+    torch.cuda.synchronize()
+    assert torch.equal(Ysub, Y[760:800])
+    # a single token takes the small-batch kernel variant, which quantises the activations differently
     Y1 = mb.mdbf_forward(dl, Xd[777:778].contiguous(), y_dtype="f32")
     torch.cuda.synchronize()
-    assert torch.equal(Y1[0], Y[777])
+    assert orc.max_rel_error(Y1[0].cpu().numpy(), Yh[777]) <= 5e-4
 
 
 # ---------------------------------------------------------------- the synthetic decoder stack
