@@ -57,7 +57,7 @@ bool mx_enabled() {
   }();
   return on;
 }
-bool use_mx(const StageProb& p) { return mx_enabled() && stage_is_fast(p) && stage_is_mx(p); }
+bool use_mx(const StageProb& p) { return mx_enabled() && stage_is_mx(p); }
 size_t layer_ws_bytes(const mdbf_desc_t* d, int T) { return z_bytes(d, T) + xs1_bytes(d, T) + xs2_bytes(d, T); }
 
 int check_layer(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
@@ -192,9 +192,9 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
     else if (use_mx(sp[i])) {
-      e = launch_scale_in_mx(nullptr, 1, T * mx_chunks(sp[i].KB), &sp[i], s);
+      e = launch_scale_in_mx(nullptr, 1, T * sp[i].KB, &sp[i], s);
       if (e) return hip_fail(e);
-      e = launch_stage_mx(nullptr, nullptr, 0, mfma_tiles_per_item(sp[i].ntiles), &sp[i], s);
+      e = launch_stage_mx(nullptr, 0, &sp[i], s);
     }
     else if (stage_is_fast(sp[i])) {
       const bool pre = sp[i].xs != nullptr;
@@ -232,13 +232,26 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
   h->magic = kPlanMagic;
   h->count = count;
   h->precise = precise ? 1 : 0;
-  // one tile count per work item for both stages keeps one kernel instantiation per plan
-  const int tpi = mfma_tiles_per_item(tiles[0] < tiles[1] ? tiles[0] : tiles[1]);
-  h->tiles_per_item = tpi;
-  long nitems[2] = {0, 0};
+  // a stage whose problems all qualify for the block-scaled variant is cut into that variant's items
+  int mx[2] = {1, 1};
   for (int i = 0; i < count; ++i) {
-    nitems[0] += (num_tiles(layers[i].desc.k) + tpi - 1) / tpi;
-    nitems[1] += (num_tiles(layers[i].desc.m) + tpi - 1) / tpi;
+    const mdbf_layer_t* L = &layers[i];
+    StageProb sp[2];
+    make_stages(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev, L->ldy, L->T,
+                (void*)(uintptr_t)256, sp);   // placeholder workspace: only the predicates are wanted
+    for (int s = 0; s < 2; ++s)
+      if (!use_mx(sp[s])) mx[s] = 0;
+  }
+  // otherwise one tile count per work item for both stages keeps one kernel instantiation per plan
+  const int tpi_fp16 = mfma_tiles_per_item(tiles[0] < tiles[1] ? tiles[0] : tiles[1]);
+  long nitems[2] = {0, 0};
+  for (int s = 0; s < 2; ++s) {
+    h->mx[s] = mx[s];
+    h->tiles_per_item[s] = mx[s] ? mx_item_tiles() : tpi_fp16;
+  }
+  for (int i = 0; i < count; ++i) {
+    nitems[0] += (num_tiles(layers[i].desc.k) + h->tiles_per_item[0] - 1) / h->tiles_per_item[0];
+    nitems[1] += (num_tiles(layers[i].desc.m) + h->tiles_per_item[1] - 1) / h->tiles_per_item[1];
   }
   if (nitems[0] > 65535 || nitems[1] > 65535) return MDBF_EUNSUPPORTED;
   h->nitems[0] = (int)nitems[0];
@@ -288,9 +301,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   int fast[2] = {1, 1};
   int pre[2] = {1, 1};
   int max_units[2] = {1, 1};
-  int mx[2] = {1, 1};
   int max_units_mx[2] = {1, 1};
-  const int tpi = h.tiles_per_item;
   for (int i = 0; i < count; ++i) {
     const mdbf_layer_t* L = &layers[i];
     StageProb sp[2];
@@ -303,8 +314,8 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
       if (!sp[s].xs) pre[s] = 0;
       const int units = sp[s].T * ((sp[s].KB + 7) / 8);
       if (units > max_units[s]) max_units[s] = units;
-      if (!use_mx(sp[s])) mx[s] = 0;
-      const int units_mx = sp[s].T * mx_chunks(sp[s].KB);
+      const int tpi = h.tiles_per_item[s];
+      const int units_mx = sp[s].T * sp[s].KB;
       if (units_mx > max_units_mx[s]) max_units_mx[s] = units_mx;
       for (int t0 = 0; t0 < sp[s].ntiles; t0 += tpi) {
         WorkItem w;
@@ -324,10 +335,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   h.pre[1] = fast[1] && pre[1];
   h.max_units[0] = max_units[0];
   h.max_units[1] = max_units[1];
-  for (int s = 0; s < 2; ++s) {
-    h.mx[s] = mx[s];
-    h.max_units_mx[s] = max_units_mx[s];
-  }
+  for (int s = 0; s < 2; ++s) h.max_units_mx[s] = max_units_mx[s];
   memcpy(base, &h, sizeof(h));
   return MDBF_OK;
 }
@@ -346,24 +354,24 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
     const WorkItem* items = (const WorkItem*)(dev + h.items_off[st]);
     StageProb dummy;
     memset(&dummy, 0, sizeof(dummy));
-    dummy.ntiles = h.tiles_per_item;
+    dummy.ntiles = h.tiles_per_item[st];
     int e;
     if (h.precise)
       e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
     else if (h.mx[st]) {
       e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
       if (e) return hip_fail(e);
-      e = launch_stage_mx(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
+      e = launch_stage_mx(items, h.nitems[st], &dummy, s);
     }
     else if (h.fast[st]) {
       if (h.pre[st]) {
         e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);
         if (e) return hip_fail(e);
       }
-      e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item, &dummy, h.pre[st] != 0, s);
+      e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item[st], &dummy, h.pre[st] != 0, s);
     }
     else
-      e = launch_stage_generic(probs, items, h.nitems[st], h.tiles_per_item, &dummy, s);
+      e = launch_stage_generic(probs, items, h.nitems[st], h.tiles_per_item[st], &dummy, s);
     if (e) return hip_fail(e);
   }
   return MDBF_OK;

@@ -74,7 +74,7 @@ struct PlanHeader {
   uint32_t magic;
   int32_t count;              // layers
   int32_t nitems[2];          // work items of stage 1 / stage 2
-  int32_t tiles_per_item;     // upper bound of WorkItem::ntiles
+  int32_t tiles_per_item[2];  // upper bound of WorkItem::ntiles, per stage
   int32_t precise;            // all layers use the fp32 path
   int32_t fast[2];            // every problem of the stage qualifies for the fast matrix-core variant
   int32_t pre[2];             // ... and has a buffer for pre-scaled activations (written by the scale-in kernel)
@@ -105,12 +105,13 @@ size_t xs_bytes_for(int K, int T);
 // Block-scaled (MX) variant of the matrix-core kernel: signs as fp4, activations as three fp6 limbs with a
 // power-of-two scale per 32 values, written by its own scale-in kernel into the same xs buffer.
 size_t xs_bytes_for_mx(int K, int T);
-int mx_chunks(int KB);                       // chunks of one token's activation stream
-bool stage_is_mx(const StageProb& p);        // on top of stage_is_fast
+int mx_item_tiles();                         // row tiles per work item of this variant
+bool stage_is_mx(const StageProb& p);        // l == 16, fp16 envelopes, an xs buffer, few tokens
+// max_units: largest tokens x blocks of a problem of the launch
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single,
                        hipStream_t s);
-int launch_stage_mx(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
-                    const StageProb* single, hipStream_t s);
+// items_dev null: one problem (`single`), items are cut on the fly
+int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s);
 constexpr int kMaxPreTokens = 16;   // token counts up to this use the scale-in kernel
 // true if the fast matrix-core variant can run the problem (l == 16, fp16 envelopes, K % 8 == 0,
 // 16-byte aligned activation rows); otherwise the general variant is used

@@ -13,15 +13,17 @@
 //    (32 values): xs' = L1*2^E + L2*2^(E-4) + L3*2^(E-8) to about 2^-13 of the block maximum, where
 //    xs' = xs / {0.5,1,2,2} undoes the value of the sign nibble.  Three MFMAs per tile and block, all into
 //    one fp32 accumulator; the hardware applies the scales.
-//  * The limbs are produced once per (problem, token) by mx_scale_in_kernel, in the order the workgroups
-//    copy them to LDS; the main kernel does no arithmetic on activations.
+//  * The limbs are produced once per (problem, token) by mx_scale_in_kernel as a stream of 5120-byte block
+//    records; the main kernel does no arithmetic on activations.
 //  * colsum[c] = sum_j xs[j,c] is taken over the quantised values by the scale-in kernel (exact in fp32 per
-//    element, one partial sum per chunk and mode) and travels at the end of each chunk record.
+//    element, one partial sum per block and mode) and travels inside each block record.
 //
-// The persistent-workgroup skeleton (units, loads of the next unit issued a chunk ahead, no load inside a
-// branch) is the one of the fp16 variant; a chunk is 6 blocks (768 columns) so that two workgroups fit a CU.
-#include <type_traits>
-
+// The main kernel is split by role.  A workgroup has four contraction waves (eight row tiles each) and one
+// loader wave.  The loader moves sign words, activation records and envelope rows from global memory
+// straight into a ring of LDS stages (global_load_lds, no registers, no waiting on its own loads beyond the
+// stage that is due) and runs two stages ahead; the contraction waves read everything from LDS and issue no
+// global loads in their loop, so a saturated memory pipeline stalls only the loader.  One barrier per stage
+// hands a filled stage to the contraction waves and a drained one back to the loader.
 #include "mdbf_internal.h"
 
 namespace mdbf {
@@ -33,36 +35,34 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define MDBF_GLOBAL __attribute__((address_space(1)))
+#define MDBF_LDS __attribute__((address_space(3)))
 typedef const MDBF_GLOBAL u32x4* g_u32x4_ptr;
 typedef const MDBF_GLOBAL uint32_t* g_u32_ptr;
 typedef const MDBF_GLOBAL uint16_t* g_u16_ptr;
 typedef const MDBF_GLOBAL float* g_f32_ptr;
 
-#ifdef MDBF_DBG_TIMING
-__device__ unsigned long long g_dbg_time_mx[64 * 64];   // [block < 64][slot]
-#define DBG_T(slot) do { if (dbg_unit == 2 && blockIdx.x < 64 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == 1 && (slot) < 64) \
-    g_dbg_time_mx[blockIdx.x * 64 + (slot)] = __builtin_readcyclecounter(); } while (0)
-#define DBG_UNIT_DECL int dbg_unit = 0
-#define DBG_UNIT_NEXT ++dbg_unit
-#else
-#define DBG_T(slot) do {} while (0)
-#define DBG_UNIT_DECL do {} while (0)
-#define DBG_UNIT_NEXT do {} while (0)
-#endif
+// ---- activation stream: one record per 128-column block
+constexpr int kLimbBytes = 64 * 24;            // 1536: [64 lanes x 16 B][64 lanes x 8 B]
+constexpr int kScaleOff = 3 * kLimbBytes;      // 4608: 64 x 4 B, scale bytes of the three limbs
+constexpr int kColsumOff = kScaleOff + 256;    // 4864: 16 fp32 column sums of the block
+constexpr int kBlockBytes = 5120;              // padded to a multiple of 1 KB (one loader instruction)
 
-constexpr int CBX = 6;                         // blocks per chunk
-// per block in the activation stream: 3 limbs x (64 x 16 B + 64 x 8 B) + 64 x 4 B of scales
-constexpr int kLimbA = 0;                      // byte offsets inside a block record
-constexpr int kLimbBytes = 64 * 24;            // 1536: [64 x 16 B][64 x 8 B]
-constexpr int kScaleOff = 3 * kLimbBytes;      // 4608
-constexpr int kBlockBytes = kScaleOff + 256;   // 4864
-constexpr int kBlockVecs = kBlockBytes / 16;   // 304
-constexpr int kColsumOff = CBX * kBlockBytes;  // 16 fp32 column sums of the chunk close its record
-constexpr int kChunkVecs = CBX * kBlockVecs + 4;           // 1828 (29248 B)
-constexpr int kCopyPerThread = (kChunkVecs + 255) / 256;   // 8
-constexpr int kBufVecs = kCopyPerThread * 256;             // LDS buffer of a chunk, padded so that copies need no mask
-__host__ __device__ constexpr int eo_vecs(int R) { return R * 4 * 16 * 2 < 256 ? 256 : R * 4 * 16 * 2; }
-__host__ __device__ constexpr int smem_bytes(int R) { return 2 * kBufVecs * 16 + eo_vecs(R) * 16; }
+// ---- main kernel geometry
+constexpr int kComputeWaves = 4;
+constexpr int R = 8;                                   // row tiles per contraction wave
+constexpr int kItemTiles = kComputeWaves * R;          // 32 row tiles per work item
+constexpr int SB = 2;                                  // blocks per stage
+constexpr int kStages = 3;                             // ring depth
+constexpr int kStageXs = SB * kBlockBytes;             // 10240
+constexpr int kStageSigns = kItemTiles * SB * 256;     // 16384: [tile][block][64 words]
+constexpr int kStageBytes = kStageXs + kStageSigns;    // 26624
+constexpr int kEoBytes = kItemTiles * kTileRows * 32;  // 16384: envelope rows of an item (fp16, 16 modes)
+static_assert(kEoBytes <= kStageBytes, "the envelope rows travel in a stage of their own");
+constexpr int kXsInstr = kStageXs / 1024;              // 10 loader instructions (64 lanes x 16 B each)
+constexpr int kSignInstr = kStageSigns / 1024;         // 16
+constexpr int kEoInstr = kEoBytes / 1024;              // 16
+constexpr int kSmemBytes = kStages * kStageBytes;      // 79872: two workgroups per compute unit
+constexpr int kThreads = 64 * (kComputeWaves + 1);
 
 // ---------------------------------------------------------------------------------------------------
 // fp6 e2m3: 1 sign, 2 exponent (bias 1), 3 mantissa bits: 0, 0.125 .. 0.875, 1 .. 1.875, 2 .. 3.75, 4 .. 7.5.
@@ -95,35 +95,34 @@ __host__ __device__ constexpr int local_col_of_element(int j, int kg) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// scale-in kernel: one workgroup per (problem, token, chunk), one wave per 128-column block.
+// scale-in kernel: one wave per (problem, token, 128-column block).
 //   1. the block's products Ein[k,c] * vin[k] (fp32; zero for k >= K) go to LDS, 128 x 16
 //   2. lane (kg, n) gathers its 32 values in operand order, undoes the nibble values, takes the block
 //      exponent E (largest magnitude <= 7.5 * 2^E) and peels three fp6 limbs at scales E, E-4, E-8;
 //      every residual is exact in fp32
-//   3. the chunk's column sums of the quantised values close the record
+//   3. the block's column sums of the quantised values close the record
 // ---------------------------------------------------------------------------------------------------
 constexpr int kProdStride = 18;   // floats per LDS row: lane groups 8 rows apart land on disjoint banks
+constexpr int kPrepWaves = 4;
 
-__global__ __launch_bounds__(64 * CBX) void mx_scale_in_kernel(const StageProb* __restrict__ probs, StageProb single) {
-  __shared__ __attribute__((aligned(16))) float prod[CBX][128 * kProdStride];
-  __shared__ float csum[CBX][16];
+__global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const StageProb* __restrict__ probs,
+                                                                      StageProb single) {
+  __shared__ __attribute__((aligned(16))) float prod[kPrepWaves][128 * kProdStride];
   StageProb p;
   if (probs) p = probs[blockIdx.y];
   else p = single;
-  const int nch = (p.KB + CBX - 1) / CBX;
-  const int unit = blockIdx.x;
-  if (unit >= nch * p.T) return;
-  const int b = unit / nch, c = unit - b * nch;
   const int tid = threadIdx.x, lane = tid & 63;
-  const int qb = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int unit = blockIdx.x * kPrepWaves + wv;        // (token, block)
+  const bool live = unit < p.KB * p.T;
+  const int b = live ? unit / p.KB : 0, q = live ? unit - b * p.KB : 0;
   const int kg = lane >> 4, n = lane & 15;
-  unsigned char* out_chunk = (unsigned char*)p.xs + ((size_t)b * nch + c) * (size_t)(kChunkVecs * 16);
-  unsigned char* blk = out_chunk + (size_t)qb * kBlockBytes;
-  const int k0 = (c * CBX + qb) * kBlockCols;
-  float* pr = prod[qb];
+  unsigned char* blk = (unsigned char*)p.xs + ((size_t)b * p.KB + q) * (size_t)kBlockBytes;
+  const int k0 = q * kBlockCols;
+  float* pr = prod[wv];
 
   // ---- 1. products: lane handles rows lane/2 + 32 i, modes 8 (lane & 1) .. + 7.  All eight loads are
-  //         issued before the first use (one memory round trip per workgroup).
+  //         issued before the first use (one memory round trip per wave).
   {
     int kc[4];
     bool in[4];
@@ -163,6 +162,7 @@ __global__ __launch_bounds__(64 * CBX) void mx_scale_in_kernel(const StageProb* 
     }
   }
   __syncthreads();
+  if (!live) return;
 
   // ---- 2. gather in operand order, quantise
   float val[32];
@@ -215,46 +215,15 @@ __global__ __launch_bounds__(64 * CBX) void mx_scale_in_kernel(const StageProb* 
   reinterpret_cast<uint32_t*>(blk + kScaleOff)[lane] =
       (uint32_t)(E + 127) | ((uint32_t)(E + 123) << 8) | ((uint32_t)(E + 119) << 16);
 
-  // ---- 3. column sums of the chunk
+  // ---- 3. column sums of the block
   part += __shfl_xor(part, 16);
   part += __shfl_xor(part, 32);
-  if (lane < 16) csum[qb][lane] = part;
-  __syncthreads();
-  if (tid < 16) {
-    float t = 0.f;
-#pragma unroll
-    for (int w = 0; w < CBX; ++w) t += csum[w][tid];
-    reinterpret_cast<float*>(out_chunk + kColsumOff)[tid] = t;
-  }
+  if (lane < 16) reinterpret_cast<float*>(blk + kColsumOff)[lane] = part;
 }
 
 // ---------------------------------------------------------------------------------------------------
 // main kernel
 // ---------------------------------------------------------------------------------------------------
-struct BlockOps {
-  u32x4 la[3];
-  u32x2 lb[3];
-  uint32_t sc;
-};
-
-__device__ __forceinline__ void load_block_ops(const unsigned char* __restrict__ blk, int lane, BlockOps& o) {
-#pragma unroll
-  for (int L = 0; L < 3; ++L) {
-    o.la[L] = reinterpret_cast<const u32x4*>(blk + L * kLimbBytes)[lane];
-    o.lb[L] = reinterpret_cast<const u32x2*>(blk + L * kLimbBytes + 64 * 16)[lane];
-  }
-  o.sc = reinterpret_cast<const uint32_t*>(blk + kScaleOff)[lane];
-}
-
-__device__ __forceinline__ v8i limb_operand(const BlockOps& o, int L) {
-  const u32x4 a = o.la[L];
-  const u32x2 b = o.lb[L];
-  v8i r;
-  r[0] = (int)a.x; r[1] = (int)a.y; r[2] = (int)a.z; r[3] = (int)a.w;
-  r[4] = (int)b.x; r[5] = (int)b.y; r[6] = 0; r[7] = 0;
-  return r;
-}
-
 __device__ __forceinline__ v8i sign_operand(uint32_t w) {
   v8i r;
   r[0] = (int)(w & 0x11111111u);
@@ -272,21 +241,6 @@ __device__ __forceinline__ floatx4 mx_mfma(v8i a, v8i b, floatx4 c, int L, uint3
   return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 2, 0, 0x7F7F7F7F, 2, (int)sc);
 }
 
-template <int R>
-__device__ __forceinline__ void contract_block(const BlockOps& o, const uint32_t (&word)[R], floatx4 (&acc)[R]) {
-  v8i bl[3];
-#pragma unroll
-  for (int L = 0; L < 3; ++L) bl[L] = limb_operand(o, L);
-  v8i a[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) a[r] = sign_operand(word[r]);
-  // limb outermost: consecutive instructions write different accumulators
-#pragma unroll
-  for (int L = 0; L < 3; ++L)
-#pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = mx_mfma(a[r], bl[L], acc[r], L, o.sc);
-}
-
 __device__ __forceinline__ float row16_sum(float v) {
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
@@ -295,287 +249,257 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
-template <int R>
-struct Unit {
-  StageProb p;
-  int tile0, ntl, b, item;
-  const uint32_t* sbase[R];
-  const u32x4* xs_tok;
+// What both roles need to know about a work item; every field is wave-uniform.
+struct ItemInfo {
+  const unsigned char* S;      // packed signs of the problem
+  const unsigned char* xs;     // activation stream of the problem (token 0)
+  const unsigned char* Eout;
+  void* out;
+  int64_t out_ld;
+  int rows, KB, T, out_dt;
+  int tile0, ntl;
 };
 
-template <int R>
-__device__ __forceinline__ void finish_unit(Unit<R>& u, int wave) {
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int trel = min(wave + 4 * r, u.ntl - 1);
-    u.sbase[r] = u.p.S + (size_t)(u.tile0 + trel) * (size_t)(u.p.KB * 64);
-  }
-  const int nch = (u.p.KB + CBX - 1) / CBX;
-  u.xs_tok = (const u32x4*)u.p.xs + (size_t)u.b * (size_t)nch * (size_t)kChunkVecs;
-}
-
-__device__ __forceinline__ uint32_t fetch_desc(const WorkItem* __restrict__ items, int item, int lane) {
-  return ((g_u32_ptr)(items + item))[lane & 31];
-}
-
-template <int R, bool BATCH>
-__device__ __forceinline__ void make_unit(uint32_t desc, const StageProb& single, int tiles_per_item, int item,
-                                          int wave, Unit<R>& u) {
+template <bool BATCH>
+__device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items, const StageProb& single, int item) {
+  ItemInfo it;
   if (BATCH) {
-    uint32_t d[28];
-#pragma unroll
-    for (int i = 0; i < 28; ++i) d[i] = __builtin_amdgcn_readlane(desc, i);
-    auto ptr = [&](int i) { return (uint64_t)d[i] | ((uint64_t)d[i + 1] << 32); };
-    u.p.S = (const uint32_t*)ptr(0);
-    u.p.Ein = (const void*)ptr(2);
-    u.p.Eout = (const void*)ptr(4);
-    u.p.vin = (const void*)ptr(6);
-    u.p.out = (void*)ptr(8);
-    u.p.xs = (void*)ptr(10);
-    u.p.vin_ld = (int64_t)ptr(12);
-    u.p.out_ld = (int64_t)ptr(14);
-    u.p.rows = (int)d[16];
-    u.p.K = (int)d[17];
-    u.p.l = (int)d[18];
-    u.p.T = (int)d[19];
-    u.p.KB = (int)d[20];
-    u.p.ntiles = (int)d[21];
-    u.p.env_dt = (int)d[22];
-    u.p.vin_dt = (int)d[23];
-    u.p.out_dt = (int)d[24];
-    u.p.pad_ = 0;
-    u.tile0 = (int)d[26];
-    u.ntl = (int)d[27];
+    const WorkItem& w = items[item];   // uniform address: scalar loads
+    it.S = (const unsigned char*)w.p.S;
+    it.xs = (const unsigned char*)w.p.xs;
+    it.Eout = (const unsigned char*)w.p.Eout;
+    it.out = w.p.out;
+    it.out_ld = w.p.out_ld;
+    it.rows = w.p.rows;
+    it.KB = w.p.KB;
+    it.T = w.p.T;
+    it.out_dt = w.p.out_dt;
+    it.tile0 = w.tile0;
+    it.ntl = w.ntiles;
   } else {
-    u.p = single;
-    u.tile0 = item * tiles_per_item;
-    u.ntl = min(tiles_per_item, single.ntiles - u.tile0);
+    it.S = (const unsigned char*)single.S;
+    it.xs = (const unsigned char*)single.xs;
+    it.Eout = (const unsigned char*)single.Eout;
+    it.out = single.out;
+    it.out_ld = single.out_ld;
+    it.rows = single.rows;
+    it.KB = single.KB;
+    it.T = single.T;
+    it.out_dt = single.out_dt;
+    it.tile0 = item * kItemTiles;
+    it.ntl = min(kItemTiles, single.ntiles - it.tile0);
   }
-  u.item = item;
-  u.b = 0;
-  finish_unit<R>(u, wave);
+  return it;
 }
 
-template <int R>
-__device__ __forceinline__ void settle(uint32_t (&wq)[R][CBX]) {
-#pragma unroll
-  for (int r = 0; r < R; ++r)
-#pragma unroll
-    for (int j = 0; j < CBX; ++j) asm volatile("" : "+v"(wq[r][j]));
+// one loader instruction: 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS at `lds`
+__device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t lane_off, unsigned char* lds) {
+  __builtin_amdgcn_global_load_lds((const MDBF_GLOBAL void*)(gbase + lane_off), (MDBF_LDS void*)lds, 16, 0, 0);
 }
 
-template <int R, bool BATCH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single, int tiles_per_item) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u32x4* buf = reinterpret_cast<u32x4*>(smem);
-  u32x4* eo = reinterpret_cast<u32x4*>(smem + 2 * kBufVecs * 16);
+// loader: blocks [q0, q0 + SB) of the item's tiles and of token b's activation stream into `stage`
+__device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, unsigned char* stage, int lane) {
+  // activation records: each record is five instructions; a block past the end repeats the last one
+#pragma unroll
+  for (int blk = 0; blk < SB; ++blk) {
+    const int q = min(q0 + blk, it.KB - 1);
+    const unsigned char* src = it.xs + ((size_t)b * it.KB + q) * (size_t)kBlockBytes;
+#pragma unroll
+    for (int i = 0; i < kBlockBytes / 1024; ++i)
+      dma16(src + i * 1024, (uint32_t)lane * 16u, stage + blk * kBlockBytes + i * 1024);
+  }
+  // sign words: instruction i carries tiles 2i, 2i+1 (lanes 0..31 / 32..63); within a tile the lane's
+  // 16 bytes are piece (lane & 31) of the tile's SB x 256 contiguous bytes
+  const int blk_of_lane = (lane >> 4) & 1;
+  const uint32_t in_tile = (uint32_t)min(q0 + blk_of_lane, it.KB - 1) * 256u + (uint32_t)(lane & 15) * 16u;
+  const size_t tile_stride = (size_t)it.KB * 256u;
+#pragma unroll
+  for (int i = 0; i < kSignInstr; ++i) {
+    const int trel = min(2 * i + (lane >> 5), it.ntl - 1);
+    const uint32_t off = (uint32_t)((size_t)trel * tile_stride) + in_tile;   // an item spans < 4 GB of signs
+    dma16(it.S + (size_t)it.tile0 * tile_stride, off, stage + kStageXs + i * 1024);
+  }
+}
 
+// loader: the item's envelope rows (16 modes, fp16: 32 bytes per row) into `stage`
+__device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane) {
+#pragma unroll
+  for (int i = 0; i < kEoInstr; ++i) {
+    const int piece = 64 * i + lane;
+    const int row = min(it.tile0 * kTileRows + (piece >> 1), it.rows - 1);
+    dma16(it.Eout, (uint32_t)row * 32u + (uint32_t)(piece & 1) * 16u, stage + i * 1024);
+  }
+}
+
+template <bool BATCH>
+__global__ __launch_bounds__(kThreads)
+void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kg = lane >> 4, n = lane & 15;
 
-  int item, i_hi, stride;
+  // ---- this workgroup's items: a contiguous range per XCD, walked with the XCD's workgroup count
+  int item0, i_hi, stride;
   if ((gridDim.x & 7) == 0) {
     const int xcd = blockIdx.x & 7;
     const int i_lo = (int)(((long)nitems * xcd) >> 3);
     i_hi = (int)(((long)nitems * (xcd + 1)) >> 3);
     stride = gridDim.x >> 3;
-    item = i_lo + (blockIdx.x >> 3);
+    item0 = i_lo + (blockIdx.x >> 3);
   } else {
     i_hi = nitems;
     stride = gridDim.x;
-    item = blockIdx.x;
+    item0 = blockIdx.x;
   }
-  if (item >= i_hi) return;
+  if (item0 >= i_hi) return;
 
-  Unit<R> u;
-  {
-    uint32_t desc0 = 0;
-    if (BATCH) desc0 = fetch_desc(items, item, lane);
-    make_unit<R, BATCH>(desc0, single, tiles_per_item, item, wave, u);
-  }
+  // Stage sequence of this workgroup, the same for both roles: for every item, for every token,
+  // ceil(KB / SB) contraction stages followed by one stage with the envelope rows.  Stage g lives in
+  // ring slot g % kStages.  Barrier g opens stage g for the contraction waves and tells the loader that
+  // stage g - 1 has been drained, so that its slot can take stage g + 2.
 
-  // ---- prologue: first sign words and first chunk of the first unit
-  uint32_t wq[R][CBX];
-#pragma unroll
-  for (int r = 0; r < R; ++r)
-#pragma unroll
-    for (int j = 0; j < CBX; ++j) wq[r][j] = ((g_u32_ptr)(u.sbase[r] + j * 64))[lane];   // KB >= CBX
-  u32x4 cp[kCopyPerThread];
-  {
-    g_u32x4_ptr src = (g_u32x4_ptr)u.xs_tok + tid;
-#pragma unroll
-    for (int i = 0; i < kCopyPerThread; ++i) cp[i] = src[min(256 * i, kChunkVecs - 1 - tid)];
-#pragma unroll
-    for (int i = 0; i < kCopyPerThread; ++i) buf[tid + 256 * i] = cp[i];
-  }
-  int par = 0;
-  __syncthreads();
-
-  DBG_UNIT_DECL;
-  for (;;) {
-    DBG_UNIT_NEXT;
-    DBG_T(0);
-    settle<R>(wq);
-    const bool next_token = (u.b + 1 < u.p.T);
-    const int ni = u.item + stride;
-    const bool has_next = next_token || (ni < i_hi);
-    uint32_t desc_next = 0;
-    if (BATCH) desc_next = fetch_desc(items, min(ni, nitems - 1), lane);
-    Unit<R> un = u;
-
-    floatx4 acc[R];
-    float colsum = 0.f;
-#pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    const int KB = u.p.KB;
-    const int nchunks = (KB + CBX - 1) / CBX;
-    uint32_t wnext[R][CBX];
-
-    // ---- all chunks but the last
-#pragma unroll 1
-    for (int c = 0; c < nchunks - 1; ++c) {
-#pragma unroll
-      for (int j = 0; j < CBX; ++j) {
-        const int qn = (c + 1) * CBX + j;
-        const uint64_t off = (qn < KB) ? (uint64_t)qn * 256u : 0u;
-#pragma unroll
-        for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)((uint64_t)u.sbase[r] + off))[lane];
+  if (wave == kComputeWaves) {
+    // =========================== loader ===========================
+    int item = item0;
+    ItemInfo it = load_item<BATCH>(items, single, item);
+    int b = 0, t = 0;                       // cursor: next stage to issue = stage t of (item, b)
+    int nst = (it.KB + SB - 1) / SB;        // contraction stages of the cursor's unit
+    bool more = true;                       // the cursor points at an existing stage
+    int slot = 0;                           // ring slot of the next stage to issue
+    int kind_prev = 0;                      // kind of the newest issued stage: 0 contraction, 1 envelope rows
+    auto issue_next = [&]() {
+      unsigned char* stage = smem + slot * kStageBytes;
+      if (t < nst) {
+        issue_stage(it, b, t * SB, stage, lane);
+        kind_prev = 0;
+      } else {
+        issue_eo(it, stage, lane);
+        kind_prev = 1;
       }
-      {
-        g_u32x4_ptr src = (g_u32x4_ptr)u.xs_tok + ((size_t)(c + 1) * kChunkVecs + tid);
-#pragma unroll
-        for (int i = 0; i < kCopyPerThread; ++i) cp[i] = src[min(256 * i, kChunkVecs - 1 - tid)];
-      }
-      DBG_T(1 + 4 * c);
-      const unsigned char* bufc = reinterpret_cast<const unsigned char*>(buf + par * kBufVecs);
-#pragma unroll
-      for (int jj = 0; jj < CBX; ++jj) {
-        uint32_t word[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) word[r] = wq[r][jj];
-        BlockOps ops;
-        load_block_ops(bufc + jj * kBlockBytes, lane, ops);
-        contract_block<R>(ops, word, acc);
-      }
-      colsum += reinterpret_cast<const float*>(bufc + kColsumOff)[n];
-      DBG_T(2 + 4 * c);
-      {
-        u32x4* dst = buf + (par ^ 1) * kBufVecs;
-#pragma unroll
-        for (int i = 0; i < kCopyPerThread; ++i) dst[tid + 256 * i] = cp[i];
-      }
-      DBG_T(3 + 4 * c);
-      __syncthreads();
-      DBG_T(4 + 4 * c);
-      par ^= 1;
-#pragma unroll
-      for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int j = 0; j < CBX; ++j) wq[r][j] = wnext[r][j];
-      settle<R>(wq);   // the wait for the prefetched words belongs here, after the chunk's contraction
-    }
-
-    // ---- the last chunk: the next unit's first chunk and this unit's Eout rows are requested up front
-    {
-      const int c = nchunks - 1;
-      settle<R>(wq);
-      asm volatile("" : "+v"(desc_next));
-      if (next_token) {
-        un.b = u.b + 1;
-        finish_unit<R>(un, wave);
-      } else if (has_next) {
-        make_unit<R, BATCH>(desc_next, single, tiles_per_item, ni, wave, un);
-      }
-#pragma unroll
-      for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int j = 0; j < CBX; ++j) wnext[r][j] = ((g_u32_ptr)(un.sbase[r] + j * 64))[lane];
-      {
-        g_u32x4_ptr src = (g_u32x4_ptr)un.xs_tok + tid;
-#pragma unroll
-        for (int i = 0; i < kCopyPerThread; ++i) cp[i] = src[min(256 * i, kChunkVecs - 1 - tid)];
-      }
-      u32x4 eoreg[eo_vecs(R) / 256];
-#pragma unroll
-      for (int t = 0; t < eo_vecs(R) / 256; ++t) {
-        const int v = tid + 256 * t;
-        const int row = min(u.tile0 * kTileRows + (v >> 1), u.p.rows - 1);
-        eoreg[t] = ((g_u32x4_ptr)u.p.Eout)[(size_t)row * 2 + (v & 1)];
-      }
-      DBG_T(1 + 4 * c);
-      const unsigned char* bufc = reinterpret_cast<const unsigned char*>(buf + par * kBufVecs);
-#pragma unroll
-      for (int jj = 0; jj < CBX; ++jj) {
-        if (c * CBX + jj < KB) {
-          uint32_t word[R];
-#pragma unroll
-          for (int r = 0; r < R; ++r) word[r] = wq[r][jj];
-          BlockOps ops;
-          load_block_ops(bufc + jj * kBlockBytes, lane, ops);
-          contract_block<R>(ops, word, acc);
+      slot = (slot + 1 == kStages) ? 0 : slot + 1;
+      // advance the cursor
+      if (t < nst) {
+        ++t;
+      } else {
+        t = 0;
+        if (b + 1 < it.T) {
+          ++b;
+        } else {
+          b = 0;
+          item += stride;
+          if (item < i_hi) {
+            it = load_item<BATCH>(items, single, item);
+            nst = (it.KB + SB - 1) / SB;
+          } else {
+            more = false;
+          }
         }
       }
-      colsum += reinterpret_cast<const float*>(bufc + kColsumOff)[n];
-      DBG_T(2 + 4 * c);
-#pragma unroll
-      for (int t = 0; t < eo_vecs(R) / 256; ++t) eo[tid + 256 * t] = eoreg[t];
-      {
-        u32x4* dst = buf + (par ^ 1) * kBufVecs;
-#pragma unroll
-        for (int i = 0; i < kCopyPerThread; ++i) dst[tid + 256 * i] = cp[i];
+    };
+    // prologue: stages 0 and 1 (every unit has at least two stages)
+    issue_next();
+    issue_next();
+    int outstanding = 2;                    // issued stages not yet handed over
+    for (;;) {
+      // hand over the oldest outstanding stage: all but the newest stage's loads must have landed
+      if (outstanding == 2) {
+        if (kind_prev == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kXsInstr + kSignInstr) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kEoInstr) : "memory");
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       }
-      DBG_T(3 + 4 * c);
-      __syncthreads();
-      DBG_T(4 + 4 * c);
-      par ^= 1;
+      asm volatile("s_barrier" ::: "memory");
+      --outstanding;
+      if (more) {
+        issue_next();
+        ++outstanding;
+      }
+      if (outstanding == 0) break;
     }
-    DBG_T(40);
+    return;
+  }
 
-    // ---- epilogue
-    const _Float16* eoh = reinterpret_cast<const _Float16*>(eo);
-    float res[R];
+  // =========================== contraction waves ===========================
+  int item = item0;
+  ItemInfo it = load_item<BATCH>(items, single, item);
+  int slot = 0;
+  for (;;) {
+    const int nr = min(R, (it.ntl - wave + kComputeWaves - 1) / kComputeWaves);   // valid tiles of this wave
+    for (int b = 0; b < it.T; ++b) {
+      floatx4 acc[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int trel = min(wave + 4 * r, u.ntl - 1);
-      float v[4];
+      for (int r = 0; r < R; ++r) acc[r] = floatx4{0.f, 0.f, 0.f, 0.f};
+      float colsum = 0.f;
+      const int nst = (it.KB + SB - 1) / SB;
+#pragma unroll 1
+      for (int t = 0; t < nst; ++t) {
+        __syncthreads();
+        const unsigned char* stage = smem + slot * kStageBytes;
+        slot = (slot + 1 == kStages) ? 0 : slot + 1;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float ev = (float)eoh[(trel * kTileRows + 4 * kg + i) * 16 + n];
-        const float P = colsum - 2.f * acc[r][i];
-        v[i] = row16_sum(ev * P);
+        for (int blk = 0; blk < SB; ++blk) {
+          if (t * SB + blk < it.KB) {
+            const unsigned char* rec = stage + blk * kBlockBytes;
+            v8i bl[3];
+#pragma unroll
+            for (int L = 0; L < 3; ++L) {
+              const u32x4 a = reinterpret_cast<const u32x4*>(rec + L * kLimbBytes)[lane];
+              const u32x2 c = reinterpret_cast<const u32x2*>(rec + L * kLimbBytes + 64 * 16)[lane];
+              bl[L][0] = (int)a.x; bl[L][1] = (int)a.y; bl[L][2] = (int)a.z; bl[L][3] = (int)a.w;
+              bl[L][4] = (int)c.x; bl[L][5] = (int)c.y; bl[L][6] = 0; bl[L][7] = 0;
+            }
+            const uint32_t sc = reinterpret_cast<const uint32_t*>(rec + kScaleOff)[lane];
+            colsum += reinterpret_cast<const float*>(rec + kColsumOff)[n];
+            const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage + kStageXs) + blk * 64 + lane;
+            v8i a[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) a[r] = sign_operand(sw[(wave + kComputeWaves * r) * SB * 64]);
+            // limb outermost: consecutive instructions write different accumulators
+#pragma unroll
+            for (int L = 0; L < 3; ++L)
+#pragma unroll
+              for (int r = 0; r < R; ++r) acc[r] = mx_mfma(a[r], bl[L], acc[r], L, sc);
+          }
+        }
       }
-      const int sel = n & 3;
-      res[r] = sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3];
+      // ---- envelope rows: fix-up, accumulate over the modes, store
+      __syncthreads();
+      {
+        const _Float16* eoh = reinterpret_cast<const _Float16*>(smem + slot * kStageBytes);
+        slot = (slot + 1 == kStages) ? 0 : slot + 1;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          if (r < nr) {
+            const int trel = wave + kComputeWaves * r;
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float ev = (float)eoh[(trel * kTileRows + 4 * kg + i) * 16 + n];
+              const float P = colsum - 2.f * acc[r][i];
+              v[i] = row16_sum(ev * P);
+            }
+            const int sel = n & 3;
+            const float res = sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3];
+            const int row = (it.tile0 + trel) * kTileRows + 4 * kg + n;
+            if (n < 4 && row < it.rows) store_from_float(it.out, (int64_t)b * it.out_ld + row, it.out_dt, res);
+          }
+        }
+      }
     }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int row = (u.tile0 + wave + 4 * r) * kTileRows + 4 * kg + n;
-      if ((wave + 4 * r) < u.ntl && n < 4 && row < u.p.rows)
-        store_from_float(u.p.out, (int64_t)u.b * u.p.out_ld + row, u.p.out_dt, res[r]);
-    }
-    DBG_T(41);
-    if (!has_next) break;
-    // a one-chunk unit writes eo again before any other barrier: wait for the slowest reader
-    if (nchunks == 1) __syncthreads();
-    u = un;
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-      for (int j = 0; j < CBX; ++j) wq[r][j] = wnext[r][j];
+    item += stride;
+    if (item >= i_hi) break;
+    it = load_item<BATCH>(items, single, item);
   }
 }
 
-template <int R, bool BATCH>
-static int launch_rb(const WorkItem* items_dev, int nitems, int tiles_per_item, const StageProb* single,
-                     hipStream_t s) {
+template <bool BATCH>
+static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
   static bool attr_set = false;
   static int max_wgs = 512;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<R, BATCH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(R));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
     if (e != hipSuccess) return (int)e;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
@@ -584,49 +508,36 @@ static int launch_rb(const WorkItem* items_dev, int nitems, int tiles_per_item, 
     attr_set = true;
   }
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
-  hipLaunchKernelGGL((stage_mx_kernel<R, BATCH>), dim3((unsigned)nwg), dim3(256), smem_bytes(R), s, items_dev,
-                     nitems, *single, tiles_per_item);
+  hipLaunchKernelGGL((stage_mx_kernel<BATCH>), dim3((unsigned)nwg), dim3(kThreads), kSmemBytes, s, items_dev, nitems,
+                     *single);
   return (int)hipGetLastError();
 }
 
 }  // namespace mx
 
-#ifdef MDBF_DBG_TIMING
-extern "C" int mdbf_dbg_read_mx(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mx::g_dbg_time_mx),
-                                  bytes < sizeof(mx::g_dbg_time_mx) ? bytes : sizeof(mx::g_dbg_time_mx));
-}
-#endif
-
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single, hipStream_t s) {
-  hipLaunchKernelGGL(mx::mx_scale_in_kernel, dim3((unsigned)max_units, (unsigned)count), dim3(64 * mx::CBX), 0, s, probs_dev,
-                     *single);
+  const int wgs = (max_units + mx::kPrepWaves - 1) / mx::kPrepWaves;
+  hipLaunchKernelGGL(mx::mx_scale_in_kernel, dim3((unsigned)wgs, (unsigned)count), dim3(64 * mx::kPrepWaves), 0, s,
+                     probs_dev, *single);
   return (int)hipGetLastError();
 }
 
-size_t xs_bytes_for_mx(int K, int T) {
-  const int nch = (num_blocks(K) + mx::CBX - 1) / mx::CBX;
-  return (size_t)T * (size_t)nch * (size_t)mx::kChunkVecs * 16u;
-}
+size_t xs_bytes_for_mx(int K, int T) { return (size_t)T * (size_t)num_blocks(K) * (size_t)mx::kBlockBytes; }
 
-int mx_chunks(int KB) { return (KB + mx::CBX - 1) / mx::CBX; }
+int mx_item_tiles() { return mx::kItemTiles; }
 
 bool stage_is_mx(const StageProb& p) {
-  return p.l == 16 && p.env_dt == MDBF_F16 && p.KB >= mx::CBX && p.xs != nullptr && p.T <= kMaxPreTokens;
+  // an item's sign words must be addressable with 32-bit offsets from its first tile
+  return p.l == 16 && p.env_dt == MDBF_F16 && p.KB >= 2 && p.xs != nullptr && p.T <= kMaxPreTokens &&
+         (size_t)mx::kItemTiles * (size_t)p.KB * 256u < (1ull << 31);
 }
 
-int launch_stage_mx(const StageProb* probs_dev, const WorkItem* items_dev, int nitems, int tiles_per_item,
-                    const StageProb* single, hipStream_t s) {
-  if (!probs_dev) nitems = (single->ntiles + tiles_per_item - 1) / tiles_per_item;
-  switch (tiles_per_item) {
-    case 4: return probs_dev ? mx::launch_rb<1, true>(items_dev, nitems, tiles_per_item, single, s)
-                             : mx::launch_rb<1, false>(items_dev, nitems, tiles_per_item, single, s);
-    case 8: return probs_dev ? mx::launch_rb<2, true>(items_dev, nitems, tiles_per_item, single, s)
-                             : mx::launch_rb<2, false>(items_dev, nitems, tiles_per_item, single, s);
-    case 16: return probs_dev ? mx::launch_rb<4, true>(items_dev, nitems, tiles_per_item, single, s)
-                              : mx::launch_rb<4, false>(items_dev, nitems, tiles_per_item, single, s);
-    default: return (int)hipErrorInvalidValue;
+int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
+  if (!items_dev) {
+    nitems = (single->ntiles + mx::kItemTiles - 1) / mx::kItemTiles;
+    return mx::launch_b<false>(nullptr, nitems, single, s);
   }
+  return mx::launch_b<true>(items_dev, nitems, single, s);
 }
 
 }  // namespace mdbf
