@@ -18,8 +18,13 @@ namespace mdbf {
 // so that, with u = w >> 8*(f/2), the word  u & ((1<<(4c+i)) | (1<<(4c+i+16))),  c = f%2,
 // viewed as two fp16 values, holds the entries (e = 2i, 2i+1) as {0 or 2^(4c+i-24)}: the
 // operand of one matrix-core step costs one AND per register and no shift.
-// Blocks of a tile are stored one after the other (256 contiguous bytes each, one word per lane):
-//   word offset of (tile t, block q, lane L), KB = blocks per tile:  (t*KB + q)*64 + L
+// Row tiles are stored in groups of 64 consecutive tiles (the last group holds what is left).  Inside a
+// group the order is block-major: all tiles' words of block 0, then of block 1, ...  so that a workgroup
+// that contracts a range of a group's tiles reads one contiguous run per block, and consecutive blocks
+// follow each other (long sequential runs; a tile-major order puts a power-of-two stride between tiles for
+// power-of-two K, which aliases HBM channels):
+//   word offset of (tile t, block q, lane L), KB = blocks per row, g0 = 64*(t/64), Gt = min(64, tiles - g0):
+//       (g0*KB + q*Gt + (t - g0))*64 + L
 // Padding rows/columns hold bit 0.
 // ---------------------------------------------------------------------------------------
 constexpr int kTileRows = 16;
@@ -30,8 +35,19 @@ __host__ __device__ inline int num_blocks(int cols) { return (cols + kBlockCols 
 __host__ __device__ inline size_t packed_words(int rows, int cols) {
   return (size_t)num_tiles(rows) * (size_t)num_blocks(cols) * 64u;
 }
-__host__ __device__ inline size_t word_offset(int tile, int q, int lane, int KB) {
-  return ((size_t)tile * (size_t)KB + (size_t)q) * 64u + (size_t)lane;
+constexpr int kGroupTiles = 64;
+// tiles in the group that holds `tile`
+__host__ __device__ inline int group_tiles(int tile, int ntiles) {
+  const int g0 = tile & ~(kGroupTiles - 1);
+  return ntiles - g0 < kGroupTiles ? ntiles - g0 : kGroupTiles;
+}
+// word offset of (tile, block 0, lane 0); consecutive blocks of the tile are group_tiles()*64 words apart
+__host__ __device__ inline size_t tile_base_words(int tile, int KB) {
+  const int g0 = tile & ~(kGroupTiles - 1);
+  return ((size_t)g0 * (size_t)KB + (size_t)(tile - g0)) * 64u;
+}
+__host__ __device__ inline size_t word_offset(int tile, int q, int lane, int KB, int ntiles) {
+  return tile_base_words(tile, KB) + (size_t)q * (size_t)group_tiles(tile, ntiles) * 64u + (size_t)lane;
 }
 // bit index of local column kl (0..127) inside its lane's word, and the lane's 8-column group
 __host__ __device__ inline int bit_of_local_col(int kl) {

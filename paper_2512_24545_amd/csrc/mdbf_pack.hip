@@ -29,7 +29,7 @@ __global__ void pack_kernel(const int8_t* __restrict__ signs, int rows, int cols
       if (col < cols && signs[(int64_t)row * ld + col] < 0) w |= (1u << b);
     }
   }
-  packed[word_offset(tile, q, lane, KB)] = w;
+  packed[word_offset(tile, q, lane, KB, num_tiles(rows))] = w;
 }
 
 __global__ void unpack_kernel(const uint32_t* __restrict__ packed, int rows, int cols,
@@ -40,7 +40,7 @@ __global__ void unpack_kernel(const uint32_t* __restrict__ packed, int rows, int
   const int tile = row / kTileRows, r = row % kTileRows;
   const int q = col / kBlockCols, kl = col % kBlockCols;
   const int lane = kgroup_of_local_col(kl) * 16 + r;
-  const uint32_t w = packed[word_offset(tile, q, lane, KB)];
+  const uint32_t w = packed[word_offset(tile, q, lane, KB, num_tiles(rows))];
   signs[(int64_t)row * ld + col] = ((w >> bit_of_local_col(kl)) & 1u) ? (int8_t)-1 : (int8_t)1;
 }
 

@@ -275,6 +275,7 @@ template <int R>
 struct Unit {
   StageProb p;
   int tile0, ntl, b, item;
+  uint32_t bstride;      // bytes between consecutive blocks of a tile (the unit lies inside one tile group)
   const uint32_t* sbase[R];
   const void* vin_row;
   const u32x4* xs_tok;   // pre-scaled activations of the unit's token (all chunks), or null
@@ -287,8 +288,9 @@ __device__ __forceinline__ void finish_unit(Unit<R>& u, int wave) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int trel = min(wave + 4 * r, u.ntl - 1);
-    u.sbase[r] = u.p.S + (size_t)(u.tile0 + trel) * (size_t)(u.p.KB * 64);
+    u.sbase[r] = u.p.S + tile_base_words(u.tile0 + trel, u.p.KB);
   }
+  u.bstride = (uint32_t)group_tiles(u.tile0, u.p.ntiles) * 256u;
   u.vin_row = (const char*)u.p.vin + (size_t)u.b * (size_t)u.p.vin_ld * (size_t)dtype_size(u.p.vin_dt);
   const int nch = (u.p.KB + CB - 1) / CB;
   u.xs_tok = (const u32x4*)u.p.xs + (size_t)u.b * (size_t)nch * (size_t)kChunkVecs;
@@ -395,7 +397,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
   for (int r = 0; r < R; ++r)
 #pragma unroll
     for (int j = 0; j < kPrefetchBlocks; ++j)
-      wq[r][j] = ((g_u32_ptr)(u.sbase[r] + j * 64))[lane];   // KB >= 8 for every fast problem
+      wq[r][j] = ((g_u32_ptr)((uint64_t)u.sbase[r] + (uint64_t)j * u.bstride))[lane];   // KB >= 8 for every fast problem
   Stager<PRE> stg;
   stg.addr(u.p.Ein, u.vin_row, u.p.vin_dt, u.xs_tok, 0, u.p.K, ch, st_col, tid);
 #pragma unroll
@@ -446,7 +448,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
 #pragma unroll
           for (int j = (CB / kLoadSteps) * jj; j < (CB / kLoadSteps) * (jj + 1); ++j) {
             const int qn = (c + 1) * CB + j;
-            const uint64_t off = (qn < KB) ? (uint64_t)qn * 256u : 0u;
+            const uint64_t off = (qn < KB) ? (uint64_t)qn * u.bstride : 0u;
 #pragma unroll
             for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)((uint64_t)u.sbase[r] + off))[lane];
           }
@@ -503,7 +505,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
 #pragma unroll
           for (int j = (CB / kLoadSteps) * jj; j < (CB / kLoadSteps) * (jj + 1); ++j)
 #pragma unroll
-            for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)(un.sbase[r] + j * 64))[lane];
+            for (int r = 0; r < R; ++r) wnext[r][j] = ((g_u32_ptr)((uint64_t)un.sbase[r] + (uint64_t)j * un.bstride))[lane];
 #pragma unroll
           for (int part = (4 / kLoadSteps) * jj; part < (4 / kLoadSteps) * (jj + 1); ++part) stg.load_part(part);
         }

@@ -18,12 +18,12 @@
 //  * colsum[c] = sum_j xs[j,c] is taken over the quantised values by the scale-in kernel (exact in fp32 per
 //    element, one partial sum per block and mode) and travels inside each block record.
 //
-// The main kernel is split by role.  A workgroup has four contraction waves (eight row tiles each) and one
-// loader wave.  The loader moves sign words, activation records and envelope rows from global memory
-// straight into a ring of LDS stages (global_load_lds, no registers, no waiting on its own loads beyond the
-// stage that is due) and runs two stages ahead; the contraction waves read everything from LDS and issue no
-// global loads in their loop, so a saturated memory pipeline stalls only the loader.  One barrier per stage
-// hands a filled stage to the contraction waves and a drained one back to the loader.
+// The main kernel is split by role.  A workgroup has eight contraction waves (eight row tiles each) and two
+// loader waves.  The loaders move sign words, activation records and envelope rows from global memory
+// straight into a ring of three LDS stages (global_load_lds: no registers, and no waiting on their own
+// loads beyond the stage that is due) and run two stages ahead; the contraction waves read everything
+// from LDS and issue no global loads in their loop, so a saturated memory pipeline stalls only the
+// loaders.  One barrier per stage hands a filled stage to the contraction waves and a drained one back.
 #include "mdbf_internal.h"
 
 namespace mdbf {
@@ -48,21 +48,30 @@ constexpr int kColsumOff = kScaleOff + 256;    // 4864: 16 fp32 column sums of t
 constexpr int kBlockBytes = 5120;              // padded to a multiple of 1 KB (one loader instruction)
 
 // ---- main kernel geometry
-constexpr int kComputeWaves = 4;
+#ifndef MDBF_MX_WAVES
+#define MDBF_MX_WAVES 8
+#endif
+constexpr int kComputeWaves = MDBF_MX_WAVES;
 constexpr int R = 8;                                   // row tiles per contraction wave
-constexpr int kItemTiles = kComputeWaves * R;          // 32 row tiles per work item
+constexpr int kItemTiles = kComputeWaves * R;          // row tiles per work item
+static_assert(kGroupTiles % kItemTiles == 0, "an item lies inside one group of the packed layout");
 constexpr int SB = 2;                                  // blocks per stage
 constexpr int kStages = 3;                             // ring depth
-constexpr int kStageXs = SB * kBlockBytes;             // 10240
-constexpr int kStageSigns = kItemTiles * SB * 256;     // 16384: [tile][block][64 words]
-constexpr int kStageBytes = kStageXs + kStageSigns;    // 26624
-constexpr int kEoBytes = kItemTiles * kTileRows * 32;  // 16384: envelope rows of an item (fp16, 16 modes)
+constexpr int kStageXs = SB * kBlockBytes;
+constexpr int kStageSigns = kItemTiles * SB * 256;     // [block][tile][64 words]
+constexpr int kStageBytes = kStageXs + kStageSigns;
+constexpr int kEoBytes = kItemTiles * kTileRows * 32;  // envelope rows of an item (fp16, 16 modes)
 static_assert(kEoBytes <= kStageBytes, "the envelope rows travel in a stage of their own");
-constexpr int kXsInstr = kStageXs / 1024;              // 10 loader instructions (64 lanes x 16 B each)
-constexpr int kSignInstr = kStageSigns / 1024;         // 16
-constexpr int kEoInstr = kEoBytes / 1024;              // 16
-constexpr int kSmemBytes = kStages * kStageBytes;      // 79872: two workgroups per compute unit
-constexpr int kThreads = 64 * (kComputeWaves + 1);
+constexpr int kXsInstr = kStageXs / 1024;              // loader instructions (64 lanes x 16 B each)
+constexpr int kSignInstr = kStageSigns / 1024;
+constexpr int kEoInstr = kEoBytes / 1024;
+constexpr int kSmemBytes = kStages * kStageBytes;
+constexpr int kWgsPerCu = (160 * 1024) / kSmemBytes;   // workgroups of this kernel a compute unit holds
+constexpr int kLoaderWaves = kComputeWaves / 4;        // a wave keeps at most 63 loads in flight
+constexpr int kThreads = 64 * (kComputeWaves + kLoaderWaves);
+static_assert(kXsInstr % kLoaderWaves == 0 && kSignInstr % kLoaderWaves == 0 && kEoInstr % kLoaderWaves == 0,
+              "the loader waves split every stage evenly");
+static_assert(2 * (kXsInstr + kSignInstr) / kLoaderWaves <= 63, "two stages in flight must fit the counter");
 
 // ---------------------------------------------------------------------------------------------------
 // fp6 e2m3: 1 sign, 2 exponent (bias 1), 3 mantissa bits: 0, 0.125 .. 0.875, 1 .. 1.875, 2 .. 3.75, 4 .. 7.5.
@@ -258,6 +267,7 @@ struct ItemInfo {
   int64_t out_ld;
   int rows, KB, T, out_dt;
   int tile0, ntl;
+  int gt;                      // tiles in the packed layout's group that holds the item
 };
 
 template <bool BATCH>
@@ -276,6 +286,7 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.out_dt = w.p.out_dt;
     it.tile0 = w.tile0;
     it.ntl = w.ntiles;
+    it.gt = group_tiles(w.tile0, w.p.ntiles);
   } else {
     it.S = (const unsigned char*)single.S;
     it.xs = (const unsigned char*)single.xs;
@@ -288,6 +299,7 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.out_dt = single.out_dt;
     it.tile0 = item * kItemTiles;
     it.ntl = min(kItemTiles, single.ntiles - it.tile0);
+    it.gt = group_tiles(it.tile0, single.ntiles);
   }
   return it;
 }
@@ -297,37 +309,76 @@ __device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t lane_
   __builtin_amdgcn_global_load_lds((const MDBF_GLOBAL void*)(gbase + lane_off), (MDBF_LDS void*)lds, 16, 0, 0);
 }
 
-// loader: blocks [q0, q0 + SB) of the item's tiles and of token b's activation stream into `stage`
-__device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, unsigned char* stage, int lane) {
+// loader wave lw (it takes every kLoaderWaves-th instruction): blocks [q0, q0 + SB) of the item's tiles and
+// of token b's activation stream into `stage`
+__device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, unsigned char* stage, int lane,
+                                            int lw) {
   // activation records: each record is five instructions; a block past the end repeats the last one
 #pragma unroll
-  for (int blk = 0; blk < SB; ++blk) {
+  for (int j = 0; j < kXsInstr / kLoaderWaves; ++j) {
+    const int i = j * kLoaderWaves + lw;
+    const int blk = i / (kBlockBytes / 1024), part = i - blk * (kBlockBytes / 1024);
     const int q = min(q0 + blk, it.KB - 1);
     const unsigned char* src = it.xs + ((size_t)b * it.KB + q) * (size_t)kBlockBytes;
-#pragma unroll
-    for (int i = 0; i < kBlockBytes / 1024; ++i)
-      dma16(src + i * 1024, (uint32_t)lane * 16u, stage + blk * kBlockBytes + i * 1024);
+    dma16(src + part * 1024, (uint32_t)lane * 16u, stage + i * 1024);
   }
-  // sign words: instruction i carries tiles 2i, 2i+1 (lanes 0..31 / 32..63); within a tile the lane's
-  // 16 bytes are piece (lane & 31) of the tile's SB x 256 contiguous bytes
-  const int blk_of_lane = (lane >> 4) & 1;
-  const uint32_t in_tile = (uint32_t)min(q0 + blk_of_lane, it.KB - 1) * 256u + (uint32_t)(lane & 15) * 16u;
-  const size_t tile_stride = (size_t)it.KB * 256u;
+  // sign words: in the packed layout the item's tiles of one block are contiguous (256 bytes per tile);
+  // instruction i carries four tiles of one block, 16 bytes per lane.  Tiles past the item's end repeat
+  // its last tile, a block past the end repeats the last block.
+  const unsigned char* ibase = it.S + tile_base_words(it.tile0, it.KB) * 4u;
+  const uint32_t bstride = (uint32_t)it.gt * 256u;
 #pragma unroll
-  for (int i = 0; i < kSignInstr; ++i) {
-    const int trel = min(2 * i + (lane >> 5), it.ntl - 1);
-    const uint32_t off = (uint32_t)((size_t)trel * tile_stride) + in_tile;   // an item spans < 4 GB of signs
-    dma16(it.S + (size_t)it.tile0 * tile_stride, off, stage + kStageXs + i * 1024);
+  for (int j = 0; j < kSignInstr / kLoaderWaves; ++j) {
+    const int i = j * kLoaderWaves + lw;
+    const int blk = i / (kItemTiles / 4);
+    const int trel = min((i - blk * (kItemTiles / 4)) * 4 + (lane >> 4), it.ntl - 1);
+    const uint32_t off = (uint32_t)min(q0 + blk, it.KB - 1) * bstride + (uint32_t)trel * 256u + (uint32_t)(lane & 15) * 16u;
+    dma16(ibase, off, stage + kStageXs + i * 1024);
   }
 }
 
 // loader: the item's envelope rows (16 modes, fp16: 32 bytes per row) into `stage`
-__device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane) {
+__device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane, int lw) {
 #pragma unroll
-  for (int i = 0; i < kEoInstr; ++i) {
+  for (int j = 0; j < kEoInstr / kLoaderWaves; ++j) {
+    const int i = j * kLoaderWaves + lw;
     const int piece = 64 * i + lane;
     const int row = min(it.tile0 * kTileRows + (piece >> 1), it.rows - 1);
     dma16(it.Eout, (uint32_t)row * 32u + (uint32_t)(piece & 1) * 16u, stage + i * 1024);
+  }
+}
+
+// one 128-column block of a stage: R tiles of this wave against the block's three limbs.  Tiles past the
+// item's end are contracted too (their sign words repeat the last tile's; the results are not stored):
+// skipping them costs more registers and branches than it saves.
+__device__ __forceinline__ void contract_block(const unsigned char* stage, int blk, int lane, int n, int wave,
+                                               floatx4 (&acc)[R], float& colsum) {
+  const unsigned char* rec = stage + blk * kBlockBytes;
+  v8i bl[3];
+#pragma unroll
+  for (int L = 0; L < 3; ++L) {
+    const u32x4 a = reinterpret_cast<const u32x4*>(rec + L * kLimbBytes)[lane];
+    const u32x2 c = reinterpret_cast<const u32x2*>(rec + L * kLimbBytes + 64 * 16)[lane];
+    bl[L][0] = (int)a.x; bl[L][1] = (int)a.y; bl[L][2] = (int)a.z; bl[L][3] = (int)a.w;
+    bl[L][4] = (int)c.x; bl[L][5] = (int)c.y; bl[L][6] = 0; bl[L][7] = 0;
+  }
+  const uint32_t sc = reinterpret_cast<const uint32_t*>(rec + kScaleOff)[lane];
+  colsum += reinterpret_cast<const float*>(rec + kColsumOff)[n];
+  const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage + kStageXs) + blk * kItemTiles * 64 + lane;
+  v8i a[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) a[r] = sign_operand(sw[(wave + kComputeWaves * r) * 64]);
+  // limb outermost: consecutive instructions write different accumulators
+#pragma unroll
+  for (int L = 0; L < 3; ++L) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#ifdef MDBF_DBG_NOMFMA
+      acc[r][0] += __builtin_bit_cast(float, a[r][0] ^ a[r][1] ^ a[r][2] ^ a[r][3] ^ bl[L][0] ^ bl[L][3] ^ bl[L][5] ^ (int)sc);
+#else
+      acc[r] = mx_mfma(a[r], bl[L], acc[r], L, sc);
+#endif
+    }
   }
 }
 
@@ -359,7 +410,8 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   // ring slot g % kStages.  Barrier g opens stage g for the contraction waves and tells the loader that
   // stage g - 1 has been drained, so that its slot can take stage g + 2.
 
-  if (wave == kComputeWaves) {
+  if (wave >= kComputeWaves) {
+    const int lw = wave - kComputeWaves;
     // =========================== loader ===========================
     int item = item0;
     ItemInfo it = load_item<BATCH>(items, single, item);
@@ -371,10 +423,10 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
     auto issue_next = [&]() {
       unsigned char* stage = smem + slot * kStageBytes;
       if (t < nst) {
-        issue_stage(it, b, t * SB, stage, lane);
+        issue_stage(it, b, t * SB, stage, lane, lw);
         kind_prev = 0;
       } else {
-        issue_eo(it, stage, lane);
+        issue_eo(it, stage, lane, lw);
         kind_prev = 1;
       }
       slot = (slot + 1 == kStages) ? 0 : slot + 1;
@@ -404,8 +456,8 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
     for (;;) {
       // hand over the oldest outstanding stage: all but the newest stage's loads must have landed
       if (outstanding == 2) {
-        if (kind_prev == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kXsInstr + kSignInstr) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kEoInstr) : "memory");
+        if (kind_prev == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kXsInstr + kSignInstr) / kLoaderWaves) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kEoInstr / kLoaderWaves) : "memory");
       } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       }
@@ -439,27 +491,12 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
         slot = (slot + 1 == kStages) ? 0 : slot + 1;
 #pragma unroll
         for (int blk = 0; blk < SB; ++blk) {
+#ifdef MDBF_DBG_NOCOMPUTE
+          if (false) {
+#else
           if (t * SB + blk < it.KB) {
-            const unsigned char* rec = stage + blk * kBlockBytes;
-            v8i bl[3];
-#pragma unroll
-            for (int L = 0; L < 3; ++L) {
-              const u32x4 a = reinterpret_cast<const u32x4*>(rec + L * kLimbBytes)[lane];
-              const u32x2 c = reinterpret_cast<const u32x2*>(rec + L * kLimbBytes + 64 * 16)[lane];
-              bl[L][0] = (int)a.x; bl[L][1] = (int)a.y; bl[L][2] = (int)a.z; bl[L][3] = (int)a.w;
-              bl[L][4] = (int)c.x; bl[L][5] = (int)c.y; bl[L][6] = 0; bl[L][7] = 0;
-            }
-            const uint32_t sc = reinterpret_cast<const uint32_t*>(rec + kScaleOff)[lane];
-            colsum += reinterpret_cast<const float*>(rec + kColsumOff)[n];
-            const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage + kStageXs) + blk * 64 + lane;
-            v8i a[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) a[r] = sign_operand(sw[(wave + kComputeWaves * r) * SB * 64]);
-            // limb outermost: consecutive instructions write different accumulators
-#pragma unroll
-            for (int L = 0; L < 3; ++L)
-#pragma unroll
-              for (int r = 0; r < R; ++r) acc[r] = mx_mfma(a[r], bl[L], acc[r], L, sc);
+#endif
+            contract_block(stage, blk, lane, n, wave, acc, colsum);
           }
         }
       }
@@ -504,7 +541,7 @@ static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* sing
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      max_wgs = 2 * cus;
+      max_wgs = kWgsPerCu * cus;
     attr_set = true;
   }
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
@@ -529,7 +566,7 @@ int mx_item_tiles() { return mx::kItemTiles; }
 bool stage_is_mx(const StageProb& p) {
   // an item's sign words must be addressable with 32-bit offsets from its first tile
   return p.l == 16 && p.env_dt == MDBF_F16 && p.KB >= 2 && p.xs != nullptr && p.T <= kMaxPreTokens &&
-         (size_t)mx::kItemTiles * (size_t)p.KB * 256u < (1ull << 31);
+         (size_t)kGroupTiles * (size_t)p.KB * 256u < (1ull << 31);
 }
 
 int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
