@@ -54,6 +54,9 @@ typedef enum { MDBF_F16 = 0, MDBF_BF16 = 1, MDBF_F32 = 2 } mdbf_dtype;
 
 /* flags of mdbf_desc_t */
 #define MDBF_FLAG_PRECISE 1u   /* fp32 vector arithmetic throughout (no fp16 staging, no matrix cores); slow */
+#define MDBF_FLAG_BLOCK_SCALED 2u /* take the block-scaled matrix-core variant wherever it applies (l = 16, fp16
+                                     envelopes, T <= 16), also for launches too small to fill the device with it;
+                                     without the flag the library picks the variant by launch size */
 
 typedef struct {
   int32_t m, n, k, l;      /* What is m x n, inner rank k, envelope rank l */

@@ -15,6 +15,7 @@ from . import build as _build
 
 MDBF_F16, MDBF_BF16, MDBF_F32 = 0, 1, 2
 MDBF_FLAG_PRECISE = 1
+MDBF_FLAG_BLOCK_SCALED = 2
 DTYPE_CODE = {"f16": MDBF_F16, "bf16": MDBF_BF16, "f32": MDBF_F32}
 
 STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE", -4: "MDBF_EWORKSPACE",
@@ -173,9 +174,10 @@ class DeviceLayer:
         env = [up(layer[kname]).to(dt).contiguous() for kname in ("A", "Q", "G", "B")]
         return DeviceLayer(layer["m"], layer["n"], layer["k"], layer["l"], SA, SB, *env)
 
-    def desc(self, x_dtype, y_dtype, precise=False):
+    def desc(self, x_dtype, y_dtype, precise=False, block_scaled=False):
+        flags = (MDBF_FLAG_PRECISE if precise else 0) | (MDBF_FLAG_BLOCK_SCALED if block_scaled else 0)
         return Desc(self.m, self.n, self.k, self.l, DTYPE_CODE[x_dtype], DTYPE_CODE[self.env_dtype],
-                    DTYPE_CODE[y_dtype], MDBF_FLAG_PRECISE if precise else 0)
+                    DTYPE_CODE[y_dtype], flags)
 
     def env(self):
         return Env(self.A.data_ptr(), self.Q.data_ptr(), self.G.data_ptr(), self.B.data_ptr())
@@ -187,12 +189,12 @@ def mdbf_workspace_bytes(desc, T):
     return out.value
 
 
-def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None, stream=None):
+def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None, stream=None, block_scaled=False):
     """Y[b,:] = What X[b,:].  X: CUDA tensor (T, n) of f16/bf16/f32; returns Y (T, m) of y_dtype."""
     torch = _torch()
     assert X.is_cuda and X.dim() == 2 and X.shape[1] == layer.n and X.stride(1) == 1
     T = X.shape[0]
-    d = layer.desc(_dtype_name(X), y_dtype, precise)
+    d = layer.desc(_dtype_name(X), y_dtype, precise, block_scaled)
     if Y is None:
         Y = torch.empty((T, layer.m), dtype=_torch_dtype(y_dtype), device=X.device)
     if workspace is None:
@@ -207,13 +209,13 @@ def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None,
 class BatchPlan:
     """Plan for many independent layers: two launches for all of them."""
 
-    def __init__(self, layers, Xs, Ys, precise=False):
+    def __init__(self, layers, Xs, Ys, precise=False, block_scaled=False):
         torch = _torch()
         assert len(layers) == len(Xs) == len(Ys) and len(layers) > 0
         n = len(layers)
         arr = (Layer * n)()
         for i, (L, X, Y) in enumerate(zip(layers, Xs, Ys)):
-            arr[i].desc = L.desc(_dtype_name(X), _dtype_name(Y), precise)
+            arr[i].desc = L.desc(_dtype_name(X), _dtype_name(Y), precise, block_scaled)
             arr[i].SA_packed_dev = L.SA_packed.data_ptr()
             arr[i].SB_packed_dev = L.SB_packed.data_ptr()
             arr[i].env = L.env()

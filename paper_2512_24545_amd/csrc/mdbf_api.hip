@@ -30,7 +30,7 @@ int check_desc(const mdbf_desc_t* d) {
   if (d->m <= 0 || d->n <= 0 || d->k <= 0) return MDBF_EINVAL;
   if (d->l < 1 || d->l > MDBF_MAX_L) return MDBF_EINVAL;
   if (!valid_dtype(d->x_dtype) || !valid_dtype(d->env_dtype) || !valid_dtype(d->y_dtype)) return MDBF_EDTYPE;
-  if (d->flags & ~MDBF_FLAG_PRECISE) return MDBF_EUNSUPPORTED;
+  if (d->flags & ~(MDBF_FLAG_PRECISE | MDBF_FLAG_BLOCK_SCALED)) return MDBF_EUNSUPPORTED;
   return MDBF_OK;
 }
 
@@ -58,6 +58,13 @@ bool mx_enabled() {
   return on;
 }
 bool use_mx(const StageProb& p) { return mx_enabled() && stage_is_mx(p); }
+// The block-scaled kernel walks the contraction dimension in stages of fixed latency and shares one copy of
+// the activation stream among 64 row tiles: it pays off when the launch has enough row tiles to give every
+// workgroup slot of the device an item.  Smaller launches (a single layer) go to the fp16 variant, whose
+// items are 4 to 16 tiles.
+bool mx_worthwhile(long launch_tiles) {
+  return launch_tiles >= (long)mx_item_tiles() * (long)mx_max_workgroups();
+}
 size_t layer_ws_bytes(const mdbf_desc_t* d, int T) { return z_bytes(d, T) + xs1_bytes(d, T) + xs2_bytes(d, T); }
 
 int check_layer(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
@@ -191,7 +198,7 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
     int e;
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
-    else if (use_mx(sp[i])) {
+    else if (use_mx(sp[i]) && ((desc->flags & MDBF_FLAG_BLOCK_SCALED) || mx_worthwhile(sp[i].ntiles))) {
       e = launch_scale_in_mx(nullptr, 1, T * sp[i].KB, &sp[i], s);
       if (e) return hip_fail(e);
       e = launch_stage_mx(nullptr, 0, &sp[i], s);
@@ -242,6 +249,10 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
     for (int s = 0; s < 2; ++s)
       if (!use_mx(sp[s])) mx[s] = 0;
   }
+  int forced = 0;
+  for (int i = 0; i < count; ++i) forced += (layers[i].desc.flags & MDBF_FLAG_BLOCK_SCALED) ? 1 : 0;
+  for (int s = 0; s < 2; ++s)
+    if (forced != count && !mx_worthwhile(tiles[s])) mx[s] = 0;
   // otherwise one tile count per work item for both stages keeps one kernel instantiation per plan
   const int tpi_fp16 = mfma_tiles_per_item(tiles[0] < tiles[1] ? tiles[0] : tiles[1]);
   long nitems[2] = {0, 0};

@@ -122,6 +122,7 @@ size_t xs_bytes_for(int K, int T);
 // power-of-two scale per 32 values, written by its own scale-in kernel into the same xs buffer.
 size_t xs_bytes_for_mx(int K, int T);
 int mx_item_tiles();                         // row tiles per work item of this variant
+int mx_max_workgroups();                     // workgroups of this variant the current device holds at once
 bool stage_is_mx(const StageProb& p);        // l == 16, fp16 envelopes, an xs buffer, few tokens
 // max_units: largest tokens x blocks of a problem of the launch
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single,

@@ -530,20 +530,29 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   }
 }
 
-template <bool BATCH>
-static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
-  static bool attr_set = false;
-  static int max_wgs = 512;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
-    if (e != hipSuccess) return (int)e;
+static int max_workgroups() {
+  static int max_wgs = 0;
+  if (!max_wgs) {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       max_wgs = kWgsPerCu * cus;
+    else
+      max_wgs = kWgsPerCu * 256;
+  }
+  return max_wgs;
+}
+
+template <bool BATCH>
+static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+    if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
+  const int max_wgs = max_workgroups();
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
   hipLaunchKernelGGL((stage_mx_kernel<BATCH>), dim3((unsigned)nwg), dim3(kThreads), kSmemBytes, s, items_dev, nitems,
                      *single);
@@ -562,6 +571,8 @@ int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, con
 size_t xs_bytes_for_mx(int K, int T) { return (size_t)T * (size_t)num_blocks(K) * (size_t)mx::kBlockBytes; }
 
 int mx_item_tiles() { return mx::kItemTiles; }
+
+int mx_max_workgroups() { return mx::max_workgroups(); }
 
 bool stage_is_mx(const StageProb& p) {
   // an item's sign words must be addressable with 32-bit offsets from its first tile

@@ -33,11 +33,11 @@ def _to_dev(torch, X, dtype):
     return torch.from_numpy(np.ascontiguousarray(X)).to("cuda:0").to(t).contiguous()
 
 
-def _run(gpu, L, X, x_dtype, y_dtype="f32", precise=False):
+def _run(gpu, L, X, x_dtype, y_dtype="f32", precise=False, block_scaled=False):
     torch, mb = gpu
     dl = mb.DeviceLayer.from_host(L)
     Xd = _to_dev(torch, X, x_dtype)
-    Y = mb.mdbf_forward(dl, Xd, y_dtype=y_dtype, precise=precise)
+    Y = mb.mdbf_forward(dl, Xd, y_dtype=y_dtype, precise=precise, block_scaled=block_scaled)
     torch.cuda.synchronize()
     return Y.float().cpu().numpy().astype(np.float64)
 
@@ -130,6 +130,73 @@ def test_exact_integer_inputs_bit_for_bit(gpu, m, n, k, l):
     assert np.max(np.abs(ref)) < 2 ** 24
     got = _run(gpu, L, X, "f16", "f32")
     np.testing.assert_array_equal(got, ref)
+
+
+# ---------------------------------------------------------------- the block-scaled variant, forced
+# (without the flag the library takes it only for launches that fill the device: the bench-sized plans)
+BLOCK_SCALED = [
+    # m, n, k, T: ragged K, one or many stages, partial tile groups, several items per matrix
+    (16, 128, 16, 1),
+    (40, 300, 70, 2),
+    (530, 2100, 1100, 3),
+    (1100, 1030, 2105, 1),
+    (2064, 520, 4100, 16),
+    (4096, 4096, 2656, 1),
+]
+
+
+@pytest.mark.parametrize("m,n,k,T", BLOCK_SCALED)
+def test_block_scaled_shapes(gpu, m, n, k, T):
+    L = synth.make_layer(m, n, k, 16, seed=m + 3 * n + 5 * k, env_dtype="f16", env_kind="unit", signed_env=True)
+    X = synth.make_activations(n, T, seed=77 + m, x_dtype="f16")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, "f16", "f32", block_scaled=True)
+    assert orc.max_rel_error(got, ref) <= TOL
+
+
+@pytest.mark.parametrize("x_dtype,y_dtype", [("bf16", "bf16"), ("f32", "f32"), ("f16", "f16")])
+def test_block_scaled_dtypes(gpu, x_dtype, y_dtype):
+    L = synth.make_layer(300, 700, 450, 16, seed=23, env_dtype="f16", env_kind="llama", signed_env=True)
+    X = synth.make_activations(700, 2, seed=24, x_dtype=x_dtype)
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, x_dtype, y_dtype, block_scaled=True)
+    slack = {"f32": 0.0, "f16": 2.0 ** -11, "bf16": 2.0 ** -8}[y_dtype]
+    assert orc.max_rel_error(got, ref) <= TOL + slack
+
+
+@pytest.mark.parametrize("m,n,k", [(64, 256, 96), (530, 2100, 1100), (4096, 4096, 2656)])
+def test_block_scaled_exact_integer_inputs(gpu, m, n, k):
+    """All-ones envelopes (l = 16) and x in {-1,0,1}: the scaled activations are small integers times a
+    power of two, which three fp6 limbs under a shared exponent hold exactly; fp32 accumulation is exact
+    below 2^24.  The result must equal the oracle bit for bit."""
+    L = synth.make_layer(m, n, k, 16, seed=41 + m, env_dtype="f16", env_kind="ones")
+    X = synth.make_activations(n, 1, seed=42, x_dtype="f16", kind="ternary")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    assert np.max(np.abs(ref)) < 2 ** 24
+    got = _run(gpu, L, X, "f16", "f32", block_scaled=True)
+    np.testing.assert_array_equal(got, ref)
+
+
+def test_block_scaled_batch_equals_single_calls(gpu):
+    torch, mb = gpu
+    specs = [(530, 2104, 1104, 2), (4096, 4096, 2656, 1), (272, 1032, 4096, 16), (1100, 1030, 2105, 1)]
+    layers, Xs, Ys, refs, singles = [], [], [], [], []
+    for i, (m, n, k, T) in enumerate(specs):
+        L = synth.make_layer(m, n, k, 16, seed=300 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+        X = synth.make_activations(n, T, seed=400 + i, x_dtype="f16")
+        dl = mb.DeviceLayer.from_host(L)
+        Xd = _to_dev(torch, X, "f16")
+        layers.append(dl)
+        Xs.append(Xd)
+        Ys.append(torch.zeros((T, m), dtype=torch.float32, device="cuda:0"))
+        refs.append(orc.forward_factored(*_oracle_args(L), X))
+        singles.append(mb.mdbf_forward(dl, Xd, y_dtype="f32", block_scaled=True))
+    plan = mb.BatchPlan(layers, Xs, Ys, block_scaled=True)
+    plan.run()
+    torch.cuda.synchronize()
+    for Yb, Y1, ref in zip(Ys, singles, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
+        assert torch.equal(Yb, Y1)
 
 
 # ---------------------------------------------------------------- LLaMA-7B shaped layers
