@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmdbf.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["mdbf_api.hip", "mdbf_pack.hip", "mdbf_precise.hip", "mdbf_stage_mfma.hip", "mdbf_stage_mx.hip",
+SOURCES = ["mdbf_api.hip", "mdbf_pack.hip", "mdbf_precise.hip", "mdbf_stage_mfma.hip", "mdbf_stage_mx.hip", "mdbf_stage_gemm.hip",
            "mdbf_stage_generic.hip"]
 
 HIPCC_FLAGS = [

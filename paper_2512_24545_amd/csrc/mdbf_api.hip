@@ -198,6 +198,8 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
     int e;
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
+    else if (T > kMaxPreTokens && stage_is_gemm(sp[i]))
+      e = launch_stage_gemm(&sp[i], s);
     else if (use_mx(sp[i]) && ((desc->flags & MDBF_FLAG_BLOCK_SCALED) || mx_worthwhile(sp[i].ntiles))) {
       e = launch_scale_in_mx(nullptr, 1, T * sp[i].KB, &sp[i], s);
       if (e) return hip_fail(e);
@@ -249,8 +251,12 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
     for (int s = 0; s < 2; ++s)
       if (!use_mx(sp[s])) mx[s] = 0;
   }
-  int forced = 0;
-  for (int i = 0; i < count; ++i) forced += (layers[i].desc.flags & MDBF_FLAG_BLOCK_SCALED) ? 1 : 0;
+  int forced = 0, many = 0;
+  for (int i = 0; i < count; ++i) {
+    forced += (layers[i].desc.flags & MDBF_FLAG_BLOCK_SCALED) ? 1 : 0;
+    many += (layers[i].T > kMaxPreTokens) ? 1 : 0;
+  }
+  h->gemm = (many == count && !precise) ? 1 : 0;
   for (int s = 0; s < 2; ++s)
     if (forced != count && !mx_worthwhile(tiles[s])) mx[s] = 0;
   // otherwise one tile count per work item for both stages keeps one kernel instantiation per plan
@@ -360,6 +366,17 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
   if (h.magic != kPlanMagic || h.count < 1 || h.total_bytes > plan_bytes) return MDBF_EINVAL;
   const unsigned char* dev = (const unsigned char*)plan_dev;
   hipStream_t s = (hipStream_t)stream;
+  if (h.gemm) {
+    // many tokens per layer: one launch per problem and stage, from the host copy of the problems
+    const unsigned char* host = (const unsigned char*)plan_host;
+    for (int i = 0; i < h.count; ++i)
+      for (int st = 0; st < 2; ++st) {
+        const StageProb* pr = (const StageProb*)(host + h.probs_off[st]) + i;
+        int e = launch_stage_gemm(pr, s);
+        if (e) return hip_fail(e);
+      }
+    return MDBF_OK;
+  }
   for (int st = 0; st < 2; ++st) {
     const StageProb* probs = (const StageProb*)(dev + h.probs_off[st]);
     const WorkItem* items = (const WorkItem*)(dev + h.items_off[st]);

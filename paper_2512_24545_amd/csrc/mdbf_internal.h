@@ -96,6 +96,7 @@ struct PlanHeader {
   int32_t pre[2];             // ... and has a buffer for pre-scaled activations (written by the scale-in kernel)
   int32_t max_units[2];       // largest tokens x chunks of a problem of the stage (grid of the scale-in kernel)
   int32_t mx[2];              // every problem of the stage qualifies for the block-scaled variant
+  int32_t gemm;               // every layer has more than kMaxPreTokens tokens: many-token variant, per problem
   int32_t max_units_mx[2];    // grid of that variant's scale-in kernel
   uint64_t probs_off[2];      // byte offsets of StageProb[count] for stage 1 / 2
   uint64_t items_off[2];      // byte offsets of WorkItem[nitems[s]]
@@ -136,6 +137,11 @@ bool stage_is_fast(const StageProb& p);
 // tiles per work item the matrix-core kernel wants for a problem with `ntiles` row tiles when
 // `total_tiles` tiles are in flight in the same launch
 int mfma_tiles_per_item(long total_tiles);
+
+// Many-token variant: the product as a dense GEMM against the factor rebuilt on the fly (any l <= 16, any
+// dtypes and shapes); one launch per problem, grid = row blocks x token blocks.
+bool stage_is_gemm(const StageProb& p);
+int launch_stage_gemm(const StageProb* p, hipStream_t s);
 
 // dtype helpers (device)
 __device__ inline float load_as_float(const void* p, int64_t idx, int dt) {

@@ -1,0 +1,256 @@
+// Many-token evaluation of one envelope-scaled binary product on gfx950, in reconstruct order.
+//
+//   out[b, r] = sum_j W[r, j] * vin[b, j],     W[r, j] = S[r, j] * E[r, j],     E = Eout * Ein^T  (rank l)
+//
+// The same product as the other stage kernels (paper Eq. "me-dbf-basis": the factor is the sign matrix
+// modulated by a rank-l envelope), but evaluated as a dense GEMM against the reconstructed factor instead
+// of l scaled binary products: (l + T) multiply-adds per sign entry instead of l * T.  Nothing dense ever
+// reaches memory: a wave rebuilds its 16 x 128 piece of E with eight small matrix-core products
+// (contraction over the l modes), flips signs with the packed bits, rounds to fp16 and holds the piece in
+// registers as the B operand of the token product; the activations go through LDS, shared by the waves.
+//
+//  * workgroup: 4 waves; wave w owns R row tiles (16 rows each); the workgroup owns 16 * TB tokens
+//  * per 128-column block: E piece per tile = 2 x v_mfma_f32_16x16x16_f16 per 32 columns.  The products'
+//    row index is chosen so that lane (r, g) receives columns 32f + 8g + 0..7 of row r: exactly the columns
+//    whose signs sit in the lane's packed word, and exactly the B-operand slot of v_mfma_f32_16x16x32_f16
+//    for contraction step f.  No cross-lane movement between reconstruction and use.
+//  * token product: for every 16-token slab, 4 contraction steps; A operand = 8 consecutive fp16 activations
+//    read from LDS (rows swizzled by 16-byte chunks against bank conflicts)
+// Arithmetic: envelopes and activations rounded to fp16 on load, E accumulated in fp32 and rounded to fp16
+// once, token product accumulated in fp32.  Values beyond the fp16 range overflow.
+#include "mdbf_internal.h"
+
+namespace mdbf {
+namespace gemm {
+
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWaves = 4;
+constexpr int kVinBufBytes = 128 * 256;     // 16 * TB <= 128 tokens x 128 columns fp16
+constexpr int kEinBufBytes = 128 * 32;      // 128 columns x 16 modes fp16
+constexpr int kSmemBytes = 2 * (kVinBufBytes + kEinBufBytes);
+
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
+  half2v h;
+  h.x = (_Float16)lo;
+  h.y = (_Float16)hi;
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+// eight consecutive elements p[idx0 .. idx0+7] as fp16 pairs; elements at or past `nvalid` read as zero
+__device__ __forceinline__ u32x4 load8_as_half(const void* p, int64_t idx0, int nvalid, int dt) {
+  u32x4 out = {0u, 0u, 0u, 0u};
+  if (nvalid <= 0) return out;
+  const int es = dtype_size(dt);
+  const uintptr_t addr = (uintptr_t)p + (uintptr_t)idx0 * (uintptr_t)es;
+  if (nvalid >= 8 && (addr & 15u) == 0) {
+    if (dt == MDBF_F16) return *reinterpret_cast<const u32x4*>(addr);
+    if (dt == MDBF_BF16) {
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(addr);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        o[i] = pack_half2(__builtin_bit_cast(float, w[i] << 16), __builtin_bit_cast(float, w[i] & 0xFFFF0000u));
+      return u32x4{o[0], o[1], o[2], o[3]};
+    }
+    const floatx4 a = *reinterpret_cast<const floatx4*>(addr);
+    const floatx4 b = *reinterpret_cast<const floatx4*>(addr + 16);
+    return u32x4{pack_half2(a.x, a.y), pack_half2(a.z, a.w), pack_half2(b.x, b.y), pack_half2(b.z, b.w)};
+  }
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (i < nvalid) ? load_as_float(p, idx0 + i, dt) : 0.f;
+  return u32x4{pack_half2(v[0], v[1]), pack_half2(v[2], v[3]), pack_half2(v[4], v[5]), pack_half2(v[6], v[7])};
+}
+
+// R row tiles per wave, TB slabs of 16 tokens per workgroup
+template <int R, int TB>
+__global__ __launch_bounds__(64 * kWaves) void stage_gemm_kernel(StageProb p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* vin_buf = smem;                               // [2][16*TB tokens][16 chunks of 16 B], swizzled
+  unsigned char* ein_buf = smem + 2 * kVinBufBytes;            // [2][128 columns][16 modes]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, g = lane >> 4;
+  const int tile0 = (blockIdx.x * kWaves + wave) * R;          // first row tile of this wave
+  const int tok0 = blockIdx.y * (16 * TB);
+  const int KB = p.KB;
+
+  // ---- per-unit operands: Eout rows of the wave's tiles (B operand of the reconstruction), 4 modes per lane
+  half4 eo_op[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int row = (tile0 + r) * kTileRows + r16;
+    float v[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int mode = 4 * g + t;
+      v[t] = (row < p.rows && mode < p.l) ? load_as_float(p.Eout, (int64_t)row * p.l + mode, p.env_dt) : 0.f;
+    }
+    eo_op[r] = half4{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+  }
+  // sign words: tiles past the end read the last tile (their rows are never stored)
+  const uint32_t* sbase[R];
+  size_t sstride[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int t = min(tile0 + r, p.ntiles - 1);
+    sbase[r] = p.S + tile_base_words(t, KB) + lane;
+    sstride[r] = (size_t)group_tiles(t, p.ntiles) * 64u;
+  }
+
+  floatx4 acc[TB][R];
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[tb][r] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // ---- global -> register staging of one block: activations (TB/2 chunks... per thread) and envelope rows
+  constexpr int kVinChunks = (16 * TB * 16) / (64 * kWaves);   // 16-byte chunks per thread: TB
+  u32x4 vin_reg[kVinChunks];
+  u32x4 ein_reg;
+  uint32_t sw_next[R];
+  auto fetch_block = [&](int q) {
+#pragma unroll
+    for (int i = 0; i < kVinChunks; ++i) {
+      const int id = tid + 64 * kWaves * i;
+      const int tok = id >> 4, c = id & 15;
+      const int col = q * kBlockCols + c * 8;
+      const int b = tok0 + tok;
+      const int nvalid = (b < p.T) ? (p.K - col) : 0;
+      vin_reg[i] = load8_as_half(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + col, nvalid, p.vin_dt);
+    }
+    {
+      const int colr = tid >> 1, half = tid & 1;
+      const int col = q * kBlockCols + colr;
+      float v[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int mode = half * 8 + t;
+        v[t] = (col < p.K && mode < p.l) ? load_as_float(p.Ein, (int64_t)col * p.l + mode, p.env_dt) : 0.f;
+      }
+      ein_reg = u32x4{pack_half2(v[0], v[1]), pack_half2(v[2], v[3]), pack_half2(v[4], v[5]), pack_half2(v[6], v[7])};
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) sw_next[r] = sbase[r][(size_t)min(q, KB - 1) * sstride[r]];
+  };
+  auto stash_block = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < kVinChunks; ++i) {
+      const int id = tid + 64 * kWaves * i;
+      const int tok = id >> 4, c = id & 15;
+      *reinterpret_cast<u32x4*>(vin_buf + buf * kVinBufBytes + tok * 256 + ((c ^ (tok & 15)) << 4)) = vin_reg[i];
+    }
+    *reinterpret_cast<u32x4*>(ein_buf + buf * kEinBufBytes + (tid >> 1) * 32 + (tid & 1) * 16) = ein_reg;
+  };
+
+  fetch_block(0);
+  stash_block(0);
+  uint32_t sw[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
+
+#pragma unroll 1
+  for (int q = 0; q < KB; ++q) {
+    const int cur = q & 1;
+    __syncthreads();
+    if (q + 1 < KB) fetch_block(q + 1);
+
+    // ---- reconstruct this wave's pieces of W for the block: wop[r][f] = B operand of contraction step f
+    const unsigned char* ein = ein_buf + cur * kEinBufBytes;
+    half8 wop[R][4];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+      // A operands of the two reconstruction products: rows mi -> columns 32f + 8(mi/4) + mi%4 (+4)
+      const int col0 = 32 * f + 8 * (r16 >> 2) + (r16 & 3);
+      const half4 ea0 = *reinterpret_cast<const half4*>(ein + col0 * 32 + g * 8);
+      const half4 ea1 = *reinterpret_cast<const half4*>(ein + (col0 + 4) * 32 + g * 8);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
+        const floatx4 e0 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea0, eo_op[r], z4, 0, 0, 0);
+        const floatx4 e1 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea1, eo_op[r], z4, 0, 0, 0);
+        // lane (r16, g) now holds E[row r16][32f + 8g + e], e = 0..3 in e0 and 4..7 in e1.  The packed word
+        // keeps the signs of columns e = 2i and 2i+1 at bits p and p + 16, p = 8(f/2) + 4(f%2) + i.
+        const int pbase = 8 * (f >> 1) + 4 * (f & 1);
+        uint32_t w4[4];
+        w4[0] = pack_half2(e0[0], e0[1]) ^ ((sw[r] << (15 - (pbase + 0))) & 0x80008000u);
+        w4[1] = pack_half2(e0[2], e0[3]) ^ ((sw[r] << (15 - (pbase + 1))) & 0x80008000u);
+        w4[2] = pack_half2(e1[0], e1[1]) ^ ((sw[r] << (15 - (pbase + 2))) & 0x80008000u);
+        w4[3] = pack_half2(e1[2], e1[3]) ^ ((sw[r] << (15 - (pbase + 3))) & 0x80008000u);
+        wop[r][f] = __builtin_bit_cast(half8, u32x4{w4[0], w4[1], w4[2], w4[3]});
+      }
+    }
+
+    // ---- token product
+    const unsigned char* vin = vin_buf + cur * kVinBufBytes;
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int tok = tb * 16 + r16;
+#pragma unroll
+      for (int f = 0; f < 4; ++f) {
+        const int c = f * 4 + g;
+        const half8 a = *reinterpret_cast<const half8*>(vin + tok * 256 + ((c ^ (tok & 15)) << 4));
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+          acc[tb][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wop[r][f], acc[tb][r], 0, 0, 0);
+      }
+    }
+
+    if (q + 1 < KB) {
+      stash_block(cur ^ 1);
+#pragma unroll
+      for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
+    }
+  }
+
+  // ---- store: lane (r16, g) holds out[token 16 tb + 4g + i][row r16 of tile r]
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int row = (tile0 + r) * kTileRows + r16;
+    if (tile0 + r < p.ntiles && row < p.rows) {
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int b = tok0 + tb * 16 + 4 * g + i;
+          if (b < p.T) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, acc[tb][r][i]);
+        }
+    }
+  }
+}
+
+template <int R, int TB>
+static int launch_rt(const StageProb* p, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  const int rows_per_wg = kWaves * R;   // tiles
+  const unsigned gx = (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
+  const unsigned gy = (unsigned)((p->T + 16 * TB - 1) / (16 * TB));
+  hipLaunchKernelGGL((stage_gemm_kernel<R, TB>), dim3(gx, gy), dim3(64 * kWaves), kSmemBytes, s, *p);
+  return (int)hipGetLastError();
+}
+
+}  // namespace gemm
+
+bool stage_is_gemm(const StageProb& p) { return p.l >= 1 && p.l <= 16; }
+
+int launch_stage_gemm(const StageProb* p, hipStream_t s) {
+  if (p->T > 64) return gemm::launch_rt<2, 8>(p, s);
+  if (p->T > 32) return gemm::launch_rt<2, 4>(p, s);
+  if (p->T > 16) return gemm::launch_rt<1, 2>(p, s);
+  return gemm::launch_rt<1, 1>(p, s);
+}
+
+}  // namespace mdbf

@@ -297,6 +297,61 @@ def test_prefill_tokens_sampled_against_oracle(gpu, x_dtype):
     assert orc.max_rel_error(Y1[0].cpu().numpy(), Yh[777]) <= 5e-4
 
 
+# ---------------------------------------------------------------- many tokens: the reconstruct-order variant
+MANY = [
+    # m, n, k, l, T, env_dtype, x_dtype: every token-slab count, ragged shapes, all envelope ranks and dtypes
+    (16, 128, 16, 16, 17, "f16", "f16"),
+    (40, 300, 70, 3, 33, "f32", "f32"),
+    (130, 129, 257, 8, 65, "bf16", "bf16"),
+    (530, 2100, 1100, 16, 100, "f16", "f16"),
+    (100, 1030, 200, 1, 130, "f16", "f32"),
+    (1100, 520, 2105, 16, 300, "f16", "bf16"),
+]
+
+
+@pytest.mark.parametrize("m,n,k,l,T,env_dtype,x_dtype", MANY)
+def test_many_token_variant(gpu, m, n, k, l, T, env_dtype, x_dtype):
+    L = synth.make_layer(m, n, k, l, seed=7 * m + n + k, env_dtype=env_dtype, env_kind="unit", signed_env=True)
+    X = synth.make_activations(n, T, seed=55 + T, x_dtype=x_dtype)
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, x_dtype, "f32")
+    assert orc.max_rel_error(got, ref) <= TOL
+
+
+def test_many_token_exact_integer_inputs(gpu):
+    """All-ones envelopes (l = 4) and x in {-1,0,1}, 50 tokens: the rebuilt factor is +-l, every partial sum
+    is an integer below 2^11 in stage 1's fp16 operands and below 2^24 in fp32: bit for bit."""
+    m, n, k, l, T = 200, 520, 96, 4, 50
+    L = synth.make_layer(m, n, k, l, seed=61, env_dtype="f16", env_kind="ones")
+    X = synth.make_activations(n, T, seed=62, x_dtype="f16", kind="ternary")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    # stage 2 feeds z = l * P1 through fp16: exact while |z| < 2048
+    _, Z = orc.forward_factored(*_oracle_args(L), X, return_intermediates=True)
+    got = _run(gpu, L, X, "f16", "f32")
+    if np.max(np.abs(Z)) < 2048:
+        np.testing.assert_array_equal(got, ref)
+    else:
+        assert orc.max_rel_error(got, ref) <= TOL
+
+
+def test_many_token_batch(gpu):
+    torch, mb = gpu
+    specs = [(530, 2104, 1104, 16, 40), (272, 1032, 4096, 16, 17), (96, 200, 150, 5, 64)]
+    layers, Xs, Ys, refs = [], [], [], []
+    for i, (m, n, k, l, T) in enumerate(specs):
+        L = synth.make_layer(m, n, k, l, seed=500 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+        X = synth.make_activations(n, T, seed=600 + i, x_dtype="f16")
+        layers.append(mb.DeviceLayer.from_host(L))
+        Xs.append(_to_dev(torch, X, "f16"))
+        Ys.append(torch.zeros((T, m), dtype=torch.float32, device="cuda:0"))
+        refs.append(orc.forward_factored(*_oracle_args(L), X))
+    plan = mb.BatchPlan(layers, Xs, Ys)
+    plan.run()
+    torch.cuda.synchronize()
+    for Yb, ref in zip(Ys, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
+
+
 # ---------------------------------------------------------------- the synthetic decoder stack
 @pytest.mark.parametrize("budget", ["1.0", "1.5", "2.0"])
 @pytest.mark.parametrize("T", [1, 8])
