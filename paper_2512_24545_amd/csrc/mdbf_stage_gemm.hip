@@ -69,9 +69,32 @@ __device__ __forceinline__ u32x4 load8_as_half(const void* p, int64_t idx0, int 
   return u32x4{pack_half2(v[0], v[1]), pack_half2(v[2], v[3]), pack_half2(v[4], v[5]), pack_half2(v[6], v[7])};
 }
 
-// R row tiles per wave, TB slabs of 16 tokens per workgroup
-template <int R, int TB>
-__global__ __launch_bounds__(64 * kWaves) void stage_gemm_kernel(StageProb p) {
+// eight consecutive elements of known type, 16-byte aligned, no bounds to respect; fp16 pairs
+template <int DT>
+__device__ __forceinline__ u32x4 load8_vec(const void* p, int64_t idx0) {
+  if (DT == MDBF_F16) return reinterpret_cast<const u32x4*>((const _Float16*)p + idx0)[0];
+  if (DT == MDBF_BF16) {
+    const u32x4 raw = reinterpret_cast<const u32x4*>((const uint16_t*)p + idx0)[0];
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      o[i] = pack_half2(__builtin_bit_cast(float, w[i] << 16), __builtin_bit_cast(float, w[i] & 0xFFFF0000u));
+    return u32x4{o[0], o[1], o[2], o[3]};
+  }
+  const floatx4 a = reinterpret_cast<const floatx4*>((const float*)p + idx0)[0];
+  const floatx4 b = reinterpret_cast<const floatx4*>((const float*)p + idx0)[1];
+  return u32x4{pack_half2(a.x, a.y), pack_half2(a.z, a.w), pack_half2(b.x, b.y), pack_half2(b.z, b.w)};
+}
+
+// R row tiles per wave, TB slabs of 16 tokens per workgroup.  MODE 0..2: the common case -- fp16 envelopes of
+// rank 16, activations of type MODE with 16-byte aligned rows and K a multiple of 8: every load is a full
+// vector, issued without a branch (addresses are clamped, values past the end replaced by zero).  MODE 3:
+// any types, ranks and alignments, element by element.
+constexpr int kGeneric = 3;
+template <int R, int TB, int MODE>
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void stage_gemm_kernel(StageProb p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* vin_buf = smem;                               // [2][16*TB tokens][16 chunks of 16 B], swizzled
   unsigned char* ein_buf = smem + 2 * kVinBufBytes;            // [2][128 columns][16 modes]
@@ -123,10 +146,21 @@ __global__ __launch_bounds__(64 * kWaves) void stage_gemm_kernel(StageProb p) {
       const int tok = id >> 4, c = id & 15;
       const int col = q * kBlockCols + c * 8;
       const int b = tok0 + tok;
-      const int nvalid = (b < p.T) ? (p.K - col) : 0;
-      vin_reg[i] = load8_as_half(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + col, nvalid, p.vin_dt);
+      if (MODE == kGeneric) {
+        const int nvalid = (b < p.T) ? (p.K - col) : 0;
+        vin_reg[i] = load8_as_half(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + col, nvalid, p.vin_dt);
+      } else {
+        const u32x4 v = load8_vec<MODE>(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + min(col, p.K - 8));
+        const bool ok = (b < p.T) && (col < p.K);
+        vin_reg[i] = u32x4{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u};
+      }
     }
-    {
+    if (MODE != kGeneric) {
+      const int col = q * kBlockCols + (tid >> 1);
+      const u32x4 v = reinterpret_cast<const u32x4*>(p.Ein)[(size_t)min(col, p.K - 1) * 2 + (tid & 1)];
+      const bool ok = col < p.K;
+      ein_reg = u32x4{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u};
+    } else {
       const int colr = tid >> 1, half = tid & 1;
       const int col = q * kBlockCols + colr;
       float v[8];
@@ -155,22 +189,25 @@ __global__ __launch_bounds__(64 * kWaves) void stage_gemm_kernel(StageProb p) {
   uint32_t sw[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
+  fetch_block(min(1, KB - 1));
 
 #pragma unroll 1
   for (int q = 0; q < KB; ++q) {
     const int cur = q & 1;
     __syncthreads();
-    if (q + 1 < KB) fetch_block(q + 1);
 
-    // ---- reconstruct this wave's pieces of W for the block: wop[r][f] = B operand of contraction step f
+    // ---- per contraction step f (32 columns): rebuild the wave's pieces of W, wop[r] = B operand of the
+    //      token product, then run the step over all token slabs.  The steps are independent of each other,
+    //      which lets the rebuild of one step overlap the matrix-core work of the previous one.
     const unsigned char* ein = ein_buf + cur * kEinBufBytes;
-    half8 wop[R][4];
+    const unsigned char* vin = vin_buf + cur * kVinBufBytes;
 #pragma unroll
     for (int f = 0; f < 4; ++f) {
       // A operands of the two reconstruction products: rows mi -> columns 32f + 8(mi/4) + mi%4 (+4)
       const int col0 = 32 * f + 8 * (r16 >> 2) + (r16 & 3);
       const half4 ea0 = *reinterpret_cast<const half4*>(ein + col0 * 32 + g * 8);
       const half4 ea1 = *reinterpret_cast<const half4*>(ein + (col0 + 4) * 32 + g * 8);
+      half8 wop[R];
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
@@ -184,30 +221,25 @@ __global__ __launch_bounds__(64 * kWaves) void stage_gemm_kernel(StageProb p) {
         w4[1] = pack_half2(e0[2], e0[3]) ^ ((sw[r] << (15 - (pbase + 1))) & 0x80008000u);
         w4[2] = pack_half2(e1[0], e1[1]) ^ ((sw[r] << (15 - (pbase + 2))) & 0x80008000u);
         w4[3] = pack_half2(e1[2], e1[3]) ^ ((sw[r] << (15 - (pbase + 3))) & 0x80008000u);
-        wop[r][f] = __builtin_bit_cast(half8, u32x4{w4[0], w4[1], w4[2], w4[3]});
+        wop[r] = __builtin_bit_cast(half8, u32x4{w4[0], w4[1], w4[2], w4[3]});
       }
-    }
-
-    // ---- token product
-    const unsigned char* vin = vin_buf + cur * kVinBufBytes;
+      const int c = f * 4 + g;
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb) {
-      const int tok = tb * 16 + r16;
-#pragma unroll
-      for (int f = 0; f < 4; ++f) {
-        const int c = f * 4 + g;
+      for (int tb = 0; tb < TB; ++tb) {
+        const int tok = tb * 16 + r16;
         const half8 a = *reinterpret_cast<const half8*>(vin + tok * 256 + ((c ^ (tok & 15)) << 4));
 #pragma unroll
         for (int r = 0; r < R; ++r)
-          acc[tb][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wop[r][f], acc[tb][r], 0, 0, 0);
+          acc[tb][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wop[r], acc[tb][r], 0, 0, 0);
       }
     }
 
-    if (q + 1 < KB) {
-      stash_block(cur ^ 1);
+    // the block after this one was requested a whole iteration ago; park it and request the next
+    // (past the end the last block is requested again: no branch around the loads)
+    stash_block(cur ^ 1);
 #pragma unroll
-      for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
-    }
+    for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
+    fetch_block(min(q + 2, KB - 1));
   }
 
   // ---- store: lane (r16, g) holds out[token 16 tb + 4g + i][row r16 of tile r]
@@ -226,11 +258,11 @@ __global__ __launch_bounds__(64 * kWaves) void stage_gemm_kernel(StageProb p) {
   }
 }
 
-template <int R, int TB>
-static int launch_rt(const StageProb* p, hipStream_t s) {
+template <int R, int TB, int MODE>
+static int launch_rtm(const StageProb* p, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB, MODE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
@@ -238,17 +270,34 @@ static int launch_rt(const StageProb* p, hipStream_t s) {
   const int rows_per_wg = kWaves * R;   // tiles
   const unsigned gx = (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
   const unsigned gy = (unsigned)((p->T + 16 * TB - 1) / (16 * TB));
-  hipLaunchKernelGGL((stage_gemm_kernel<R, TB>), dim3(gx, gy), dim3(64 * kWaves), kSmemBytes, s, *p);
+  hipLaunchKernelGGL((stage_gemm_kernel<R, TB, MODE>), dim3(gx, gy), dim3(64 * kWaves), kSmemBytes, s, *p);
   return (int)hipGetLastError();
+}
+
+template <int R, int TB>
+static int launch_rt(const StageProb* p, hipStream_t s) {
+  const int es = dtype_size(p->vin_dt);
+  const bool fast = p->env_dt == MDBF_F16 && p->l == 16 && (p->K & 7) == 0 && p->K >= 8 &&
+                    (((uintptr_t)p->vin | (uintptr_t)p->Ein) & 15u) == 0 && ((p->vin_ld * es) & 15) == 0;
+  if (!fast) return launch_rtm<R, TB, kGeneric>(p, s);
+  if (p->vin_dt == MDBF_F16) return launch_rtm<R, TB, MDBF_F16>(p, s);
+  if (p->vin_dt == MDBF_BF16) return launch_rtm<R, TB, MDBF_BF16>(p, s);
+  return launch_rtm<R, TB, MDBF_F32>(p, s);
 }
 
 }  // namespace gemm
 
 bool stage_is_gemm(const StageProb& p) { return p.l >= 1 && p.l <= 16; }
 
+#ifndef MDBF_GEMM_R
+#define MDBF_GEMM_R 2
+#endif
+#ifndef MDBF_GEMM_TB
+#define MDBF_GEMM_TB 8
+#endif
 int launch_stage_gemm(const StageProb* p, hipStream_t s) {
-  if (p->T > 64) return gemm::launch_rt<2, 8>(p, s);
-  if (p->T > 32) return gemm::launch_rt<2, 4>(p, s);
+  if (p->T > 64) return gemm::launch_rt<MDBF_GEMM_R, MDBF_GEMM_TB>(p, s);
+  if (p->T > 32) return gemm::launch_rt<1, 4>(p, s);
   if (p->T > 16) return gemm::launch_rt<1, 2>(p, s);
   return gemm::launch_rt<1, 1>(p, s);
 }
