@@ -196,11 +196,12 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
   hipStream_t s = (hipStream_t)stream;
   for (int i = 0; i < 2; ++i) {
     int e;
+    const bool forced_mx = (desc->flags & MDBF_FLAG_BLOCK_SCALED) && use_mx(sp[i]);
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
-    else if (T > kMaxPreTokens && stage_is_gemm(sp[i]))
-      e = launch_stage_gemm(&sp[i], s);
-    else if (use_mx(sp[i]) && ((desc->flags & MDBF_FLAG_BLOCK_SCALED) || mx_worthwhile(sp[i].ntiles))) {
+    else if (!forced_mx && T >= kGemmMinTokensSingle && stage_is_gemm(sp[i]))
+      e = launch_stage_gemm(nullptr, 0, 0, &sp[i], s);
+    else if (forced_mx || (use_mx(sp[i]) && mx_worthwhile(sp[i].ntiles))) {
       e = launch_scale_in_mx(nullptr, 1, T * sp[i].KB, &sp[i], s);
       if (e) return hip_fail(e);
       e = launch_stage_mx(nullptr, 0, &sp[i], s);
@@ -254,17 +255,18 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
   int forced = 0, many = 0;
   for (int i = 0; i < count; ++i) {
     forced += (layers[i].desc.flags & MDBF_FLAG_BLOCK_SCALED) ? 1 : 0;
-    many += (layers[i].T > kMaxPreTokens) ? 1 : 0;
+    many += (layers[i].T >= kGemmMinTokensPlan) ? 1 : 0;
+    if (layers[i].T > h->max_tokens) h->max_tokens = layers[i].T;
   }
-  h->gemm = (many == count && !precise) ? 1 : 0;
+  h->gemm = (many == count && !precise && forced != count) ? 1 : 0;
   for (int s = 0; s < 2; ++s)
-    if (forced != count && !mx_worthwhile(tiles[s])) mx[s] = 0;
+    if (h->gemm || (forced != count && !mx_worthwhile(tiles[s]))) mx[s] = 0;
   // otherwise one tile count per work item for both stages keeps one kernel instantiation per plan
   const int tpi_fp16 = mfma_tiles_per_item(tiles[0] < tiles[1] ? tiles[0] : tiles[1]);
   long nitems[2] = {0, 0};
   for (int s = 0; s < 2; ++s) {
     h->mx[s] = mx[s];
-    h->tiles_per_item[s] = mx[s] ? mx_item_tiles() : tpi_fp16;
+    h->tiles_per_item[s] = h->gemm ? gemm_tiles_per_item() : mx[s] ? mx_item_tiles() : tpi_fp16;
   }
   for (int i = 0; i < count; ++i) {
     nitems[0] += (num_tiles(layers[i].desc.k) + h->tiles_per_item[0] - 1) / h->tiles_per_item[0];
@@ -319,6 +321,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   int pre[2] = {1, 1};
   int max_units[2] = {1, 1};
   int max_units_mx[2] = {1, 1};
+  int gmode[2] = {-1, -1};
   for (int i = 0; i < count; ++i) {
     const mdbf_layer_t* L = &layers[i];
     StageProb sp[2];
@@ -328,6 +331,8 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
     for (int s = 0; s < 2; ++s) {
       probs[s][i] = sp[s];
       if (!stage_is_fast(sp[s])) fast[s] = 0;
+      const int gm = gemm_load_mode(sp[s]);
+      gmode[s] = (gmode[s] == -1 || gmode[s] == gm) ? gm : 3;
       if (!sp[s].xs) pre[s] = 0;
       const int units = sp[s].T * ((sp[s].KB + 7) / 8);
       if (units > max_units[s]) max_units[s] = units;
@@ -352,7 +357,10 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   h.pre[1] = fast[1] && pre[1];
   h.max_units[0] = max_units[0];
   h.max_units[1] = max_units[1];
-  for (int s = 0; s < 2; ++s) h.max_units_mx[s] = max_units_mx[s];
+  for (int s = 0; s < 2; ++s) {
+    h.max_units_mx[s] = max_units_mx[s];
+    h.gemm_mode[s] = gmode[s];
+  }
   memcpy(base, &h, sizeof(h));
   return MDBF_OK;
 }
@@ -366,15 +374,24 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
   if (h.magic != kPlanMagic || h.count < 1 || h.total_bytes > plan_bytes) return MDBF_EINVAL;
   const unsigned char* dev = (const unsigned char*)plan_dev;
   hipStream_t s = (hipStream_t)stream;
-  if (h.gemm) {
-    // many tokens per layer: one launch per problem and stage, from the host copy of the problems
+  if (h.gemm && h.max_tokens > gemm_plan_max_tokens()) {
+    // long problems: each fills the device by itself; one launch per problem and stage, from the host copy
     const unsigned char* host = (const unsigned char*)plan_host;
     for (int i = 0; i < h.count; ++i)
       for (int st = 0; st < 2; ++st) {
-        const StageProb* pr = (const StageProb*)(host + h.probs_off[st]) + i;
-        int e = launch_stage_gemm(pr, s);
+        int e = launch_stage_gemm(nullptr, 0, 0, (const StageProb*)(host + h.probs_off[st]) + i, s);
         if (e) return hip_fail(e);
       }
+    return MDBF_OK;
+  }
+  if (h.gemm) {
+    for (int st = 0; st < 2; ++st) {
+      StageProb launch;
+      memset(&launch, 0, sizeof(launch));
+      launch.T = h.max_tokens;
+      int e = launch_stage_gemm((const WorkItem*)(dev + h.items_off[st]), h.nitems[st], h.gemm_mode[st], &launch, s);
+      if (e) return hip_fail(e);
+    }
     return MDBF_OK;
   }
   for (int st = 0; st < 2; ++st) {

@@ -96,7 +96,9 @@ struct PlanHeader {
   int32_t pre[2];             // ... and has a buffer for pre-scaled activations (written by the scale-in kernel)
   int32_t max_units[2];       // largest tokens x chunks of a problem of the stage (grid of the scale-in kernel)
   int32_t mx[2];              // every problem of the stage qualifies for the block-scaled variant
-  int32_t gemm;               // every layer has more than kMaxPreTokens tokens: many-token variant, per problem
+  int32_t gemm;               // every layer has kGemmMinTokensPlan tokens or more: many-token variant
+  int32_t gemm_mode[2];       // its load mode per stage
+  int32_t max_tokens;         // longest token count among the layers
   int32_t max_units_mx[2];    // grid of that variant's scale-in kernel
   uint64_t probs_off[2];      // byte offsets of StageProb[count] for stage 1 / 2
   uint64_t items_off[2];      // byte offsets of WorkItem[nitems[s]]
@@ -140,8 +142,20 @@ int mfma_tiles_per_item(long total_tiles);
 
 // Many-token variant: the product as a dense GEMM against the factor rebuilt on the fly (any l <= 16, any
 // dtypes and shapes); one launch per problem, grid = row blocks x token blocks.
+// Token counts from which the many-token variant is taken: a single call (one layer cannot fill the device
+// with the streaming kernels, the rebuild costs the same for 1 to 16 tokens), and a plan (the streaming
+// kernels read the signs once per token; the rebuild pays off from a few tokens on).
+constexpr int kGemmMinTokensSingle = 2;
+constexpr int kGemmMinTokensPlan = 4;
 bool stage_is_gemm(const StageProb& p);
-int launch_stage_gemm(const StageProb* p, hipStream_t s);
+// how the kernel may load the problem's operands: a dtype code (vector loads of that activation type, fp16
+// rank-16 envelopes, aligned rows) or 3 (element by element); a plan takes 3 unless all problems agree
+int gemm_load_mode(const StageProb& p);
+int gemm_tiles_per_item();
+int gemm_plan_max_tokens();
+// items_dev null: the single problem *p (mode ignored).  Else the work items of a plan (at most
+// gemm_plan_max_tokens() tokens per problem); p->T = the longest token count among its problems, mode as above.
+int launch_stage_gemm(const WorkItem* items_dev, int nitems, int mode, const StageProb* p, hipStream_t s);
 
 // dtype helpers (device)
 __device__ inline float load_as_float(const void* p, int64_t idx, int dt) {

@@ -91,18 +91,34 @@ __device__ __forceinline__ u32x4 load8_vec(const void* p, int64_t idx0) {
 // rank 16, activations of type MODE with 16-byte aligned rows and K a multiple of 8: every load is a full
 // vector, issued without a branch (addresses are clamped, values past the end replaced by zero).  MODE 3:
 // any types, ranks and alignments, element by element.
+// BATCH: the rows come from a plan's work items instead of the single problem.
 constexpr int kGeneric = 3;
-template <int R, int TB, int MODE>
+template <int R, int TB, int MODE, bool BATCH>
 __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void stage_gemm_kernel(StageProb p) {
+void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // the rows of this workgroup: a work item of a plan (at most kWaves * R row tiles of one problem), or
+  // the blockIdx.x-th run of kWaves * R tiles of the single problem
+  StageProb p;
+  int item_tile0, item_end;
+  if (BATCH) {
+    const WorkItem& w = items[blockIdx.x];   // uniform address: scalar loads
+    p = w.p;
+    item_tile0 = w.tile0;
+    item_end = w.tile0 + w.ntiles;
+  } else {
+    p = single;
+    item_tile0 = blockIdx.x * (kWaves * R);
+    item_end = min(item_tile0 + kWaves * R, p.ntiles);
+  }
   unsigned char* vin_buf = smem;                               // [2][16*TB tokens][16 chunks of 16 B], swizzled
   unsigned char* ein_buf = smem + 2 * kVinBufBytes;            // [2][128 columns][16 modes]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r16 = lane & 15, g = lane >> 4;
-  const int tile0 = (blockIdx.x * kWaves + wave) * R;          // first row tile of this wave
+  const int tile0 = item_tile0 + wave * R;                     // first row tile of this wave
   const int tok0 = blockIdx.y * (16 * TB);
+  if (tok0 >= p.T) return;                                     // a plan's grid covers its longest problem
   const int KB = p.KB;
 
   // ---- per-unit operands: Eout rows of the wave's tiles (B operand of the reconstruction), 4 modes per lane
@@ -123,7 +139,7 @@ void stage_gemm_kernel(StageProb p) {
   size_t sstride[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int t = min(tile0 + r, p.ntiles - 1);
+    const int t = min(tile0 + r, item_end - 1);
     sbase[r] = p.S + tile_base_words(t, KB) + lane;
     sstride[r] = (size_t)group_tiles(t, p.ntiles) * 64u;
   }
@@ -223,15 +239,19 @@ void stage_gemm_kernel(StageProb p) {
         w4[3] = pack_half2(e1[2], e1[3]) ^ ((sw[r] << (15 - (pbase + 3))) & 0x80008000u);
         wop[r] = __builtin_bit_cast(half8, u32x4{w4[0], w4[1], w4[2], w4[3]});
       }
+      // the step's A operands (one per token slab) are all requested before the first product
       const int c = f * 4 + g;
+      half8 a[TB];
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
         const int tok = tb * 16 + r16;
-        const half8 a = *reinterpret_cast<const half8*>(vin + tok * 256 + ((c ^ (tok & 15)) << 4));
+        a[tb] = *reinterpret_cast<const half8*>(vin + tok * 256 + ((c ^ (tok & 15)) << 4));
+      }
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
         for (int r = 0; r < R; ++r)
-          acc[tb][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wop[r], acc[tb][r], 0, 0, 0);
-      }
+          acc[tb][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[tb], wop[r], acc[tb][r], 0, 0, 0);
     }
 
     // the block after this one was requested a whole iteration ago; park it and request the next
@@ -246,7 +266,7 @@ void stage_gemm_kernel(StageProb p) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int row = (tile0 + r) * kTileRows + r16;
-    if (tile0 + r < p.ntiles && row < p.rows) {
+    if (tile0 + r < item_end && row < p.rows) {
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
@@ -258,36 +278,42 @@ void stage_gemm_kernel(StageProb p) {
   }
 }
 
-template <int R, int TB, int MODE>
-static int launch_rtm(const StageProb* p, hipStream_t s) {
+// items_dev null: the single problem *p.  Else nitems work items of a plan, `p` describing the launch:
+// p->T = the longest token count among the problems.
+template <int R, int TB, int MODE, bool BATCH>
+static int launch_rtmb(const WorkItem* items_dev, int nitems, const StageProb* p, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB, MODE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB, MODE, BATCH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
   const int rows_per_wg = kWaves * R;   // tiles
-  const unsigned gx = (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
+  const unsigned gx = BATCH ? (unsigned)nitems : (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
   const unsigned gy = (unsigned)((p->T + 16 * TB - 1) / (16 * TB));
-  hipLaunchKernelGGL((stage_gemm_kernel<R, TB, MODE>), dim3(gx, gy), dim3(64 * kWaves), kSmemBytes, s, *p);
+  hipLaunchKernelGGL((stage_gemm_kernel<R, TB, MODE, BATCH>), dim3(gx, gy), dim3(64 * kWaves), kSmemBytes, s,
+                     items_dev, *p);
   return (int)hipGetLastError();
 }
 
+// plans exist for the one-tile-per-wave shapes only (R = 1)
+template <int R, int TB, int MODE>
+static int launch_rtm(const WorkItem* items_dev, int nitems, const StageProb* p, hipStream_t s) {
+  if (R == 1 && items_dev) return launch_rtmb<1, TB, MODE, true>(items_dev, nitems, p, s);
+  if (items_dev) return (int)hipErrorInvalidValue;
+  return launch_rtmb<R, TB, MODE, false>(nullptr, 0, p, s);
+}
+
 template <int R, int TB>
-static int launch_rt(const StageProb* p, hipStream_t s) {
-  const int es = dtype_size(p->vin_dt);
-  const bool fast = p->env_dt == MDBF_F16 && p->l == 16 && (p->K & 7) == 0 && p->K >= 8 &&
-                    (((uintptr_t)p->vin | (uintptr_t)p->Ein) & 15u) == 0 && ((p->vin_ld * es) & 15) == 0;
-  if (!fast) return launch_rtm<R, TB, kGeneric>(p, s);
-  if (p->vin_dt == MDBF_F16) return launch_rtm<R, TB, MDBF_F16>(p, s);
-  if (p->vin_dt == MDBF_BF16) return launch_rtm<R, TB, MDBF_BF16>(p, s);
-  return launch_rtm<R, TB, MDBF_F32>(p, s);
+static int launch_rt(const WorkItem* items_dev, int nitems, int mode, const StageProb* p, hipStream_t s) {
+  if (mode == kGeneric) return launch_rtm<R, TB, kGeneric>(items_dev, nitems, p, s);
+  if (mode == MDBF_F16) return launch_rtm<R, TB, MDBF_F16>(items_dev, nitems, p, s);
+  if (mode == MDBF_BF16) return launch_rtm<R, TB, MDBF_BF16>(items_dev, nitems, p, s);
+  return launch_rtm<R, TB, MDBF_F32>(items_dev, nitems, p, s);
 }
 
 }  // namespace gemm
-
-bool stage_is_gemm(const StageProb& p) { return p.l >= 1 && p.l <= 16; }
 
 #ifndef MDBF_GEMM_R
 #define MDBF_GEMM_R 2
@@ -295,11 +321,24 @@ bool stage_is_gemm(const StageProb& p) { return p.l >= 1 && p.l <= 16; }
 #ifndef MDBF_GEMM_TB
 #define MDBF_GEMM_TB 8
 #endif
-int launch_stage_gemm(const StageProb* p, hipStream_t s) {
-  if (p->T > 64) return gemm::launch_rt<MDBF_GEMM_R, MDBF_GEMM_TB>(p, s);
-  if (p->T > 32) return gemm::launch_rt<1, 4>(p, s);
-  if (p->T > 16) return gemm::launch_rt<1, 2>(p, s);
-  return gemm::launch_rt<1, 1>(p, s);
+bool stage_is_gemm(const StageProb& p) { return p.l >= 1 && p.l <= 16; }
+
+int gemm_load_mode(const StageProb& p) {
+  const int es = dtype_size(p.vin_dt);
+  const bool fast = p.env_dt == MDBF_F16 && p.l == 16 && (p.K & 7) == 0 && p.K >= 8 &&
+                    (((uintptr_t)p.vin | (uintptr_t)p.Ein) & 15u) == 0 && ((p.vin_ld * es) & 15) == 0;
+  return fast ? p.vin_dt : gemm::kGeneric;
+}
+
+int gemm_tiles_per_item() { return gemm::kWaves; }
+int gemm_plan_max_tokens() { return 64; }   // plans with longer problems launch the single-problem kernel per problem
+
+int launch_stage_gemm(const WorkItem* items_dev, int nitems, int mode, const StageProb* p, hipStream_t s) {
+  if (!items_dev) mode = gemm_load_mode(*p);
+  if (p->T > 64) return gemm::launch_rt<MDBF_GEMM_R, MDBF_GEMM_TB>(items_dev, nitems, mode, p, s);
+  if (p->T > 32) return gemm::launch_rt<1, 4>(items_dev, nitems, mode, p, s);
+  if (p->T > 16) return gemm::launch_rt<1, 2>(items_dev, nitems, mode, p, s);
+  return gemm::launch_rt<1, 1>(items_dev, nitems, mode, p, s);
 }
 
 }  // namespace mdbf

@@ -231,12 +231,12 @@ def test_determinism(gpu):
 
 
 # ---------------------------------------------------------------- many layers in one launch pair
-def _batch_case(gpu, specs):
+def _batch_case(gpu, specs, tokens=lambda i: 1 + (i % 2)):
     torch, mb = gpu
     layers, Xs, Ys, singles, refs = [], [], [], [], []
     for i, (m, n, k, l) in enumerate(specs):
         L = synth.make_layer(m, n, k, l, seed=400 + i, env_dtype="f16", env_kind="llama")
-        X = synth.make_activations(n, 1 + (i % 2), seed=500 + i, x_dtype="f16")
+        X = synth.make_activations(n, tokens(i), seed=500 + i, x_dtype="f16")
         dl = mb.DeviceLayer.from_host(L)
         Xd = _to_dev(torch, X, "f16")
         layers.append(dl)
@@ -265,7 +265,17 @@ def test_batch_fast_layers_equal_single_calls(gpu):
     """All layers l = 16 / fp16: the plan and the single calls run the same kernel, bit for bit."""
     torch, mb = gpu
     specs = [(530, 2104, 1104, 16), (4096, 4096, 2656, 16), (272, 1032, 4096, 16), (4096, 4096, 2656, 16)]
-    Ys, singles, refs = _batch_case(gpu, specs)
+    Ys, singles, refs = _batch_case(gpu, specs, tokens=lambda i: 1)
+    for Yb, Y1, ref in zip(Ys, singles, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
+        assert torch.equal(Yb, Y1)
+
+
+def test_plan_of_several_tokens_equals_single_calls(gpu):
+    """From a few tokens on, plans and single calls both take the reconstruct-order variant."""
+    torch, mb = gpu
+    specs = [(530, 2104, 1104, 16), (272, 1032, 4096, 16), (96, 200, 150, 5), (4096, 4096, 2656, 16)]
+    Ys, singles, refs = _batch_case(gpu, specs, tokens=lambda i: 4 + 3 * i)
     for Yb, Y1, ref in zip(Ys, singles, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
         assert torch.equal(Yb, Y1)
