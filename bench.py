@@ -7,9 +7,10 @@ offline; scale-in, binary product 1, envelope accumulate + re-scale, binary prod
 accumulate) over one batch of `copies` INDEPENDENT layers of that shape, each with its own
 signs, envelopes and activation vector, resident in HBM.  The batch exceeds 1 GB, several times
 the 256 MB last-level cache, so every step streams its weights from HBM.  The batch is issued
-through mdbf_forward_batch (two kernel launches per step).  Also reported, never as `value`:
-the same layers issued as one mdbf_forward call each from a HIP graph, one layer re-run hot
-in cache, and the latency of a single call.
+through mdbf_forward_batch (per factor one scale-in launch and one product launch).  Also
+reported, never as `value`: the product kernel timed by itself (the roofline object), the same
+layers issued as one mdbf_forward call each from a HIP graph, one layer re-run hot in cache, the
+latency of a single call, a 16-token call on an MLP projection, and the 2048-token prefill call.
 
 Prints ONE JSON line (see README for the fields).
 """
@@ -150,9 +151,21 @@ def main():
     err, host_args = oracle_check(torch, mb, layers[0], Xs[0], Ys[0])
     err_last, _ = oracle_check(torch, mb, layers[-1], Xs[-1], Ys[-1])
 
-    # ---- roofline of the dominant kernel (the stage kernel; two launches per step)
-    launches = 2 * a.steps
-    avg_launch_ms = ms_total / launches
+    # ---- roofline of the dominant kernel: the product kernel (one launch per factor, two per step), timed
+    #      by itself over the same number of steps; the scale-in results of the last full step stay valid
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(a.steps):
+        plan.run_part(3, 2)
+    e1.record()
+    torch.cuda.synchronize()
+    avg_launch_ms = e0.elapsed_time(e1) / (2 * a.steps)
+    e0.record()
+    for _ in range(a.steps):
+        plan.run_part(3, 1)
+    e1.record()
+    torch.cuda.synchronize()
+    avg_scale_in_ms = e0.elapsed_time(e1) / (2 * a.steps)
     traffic = None   # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE runs
     tpath = os.path.join(ROOT, "profiles", "traffic_attn_decode.json")
     if os.path.exists(tpath):
@@ -160,7 +173,8 @@ def main():
             traffic = json.load(f)["hbm_bytes_per_layer_per_launch"] * a.copies
     roof = {"bound": "hbm", "kernel": "stage_mx_kernel", "achieved": (bytes_step / 2) / avg_launch_ms / 1e6,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": traffic,
-            "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_step / 2}
+            "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_step / 2,
+            "scale_in_avg_launch_us": avg_scale_in_ms * 1e3}
     roof["frac"] = roof["achieved"] / roof["peak"]
 
     extras = {}
@@ -205,6 +219,33 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         extras["single_call_stream"] = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 200}
+        del ws, g, hot
+        # (4) 16 tokens through one MLP projection (11008 x 4096, k = 4096) and (5) the 2048-token prefill
+        #     call on the attention shape: reconstruct-order kernel, bound by the fp16 matrix cores
+        from paper_2512_24545_amd import synth
+
+        def time_call(m, n, k, T, reps):
+            Lh = synth.make_layer(m, n, k, L, seed=11)
+            dl = mb.DeviceLayer.from_host(Lh)
+            X = torch.randn((T, n), device="cuda:0").half()
+            Y = torch.empty((T, m), dtype=torch.float32, device="cuda:0")
+            wsb = torch.empty(mb.mdbf_workspace_bytes(dl.desc("f16", "f32"), T), dtype=torch.uint8, device="cuda:0")
+            for _ in range(reps):
+                mb.mdbf_forward(dl, X, y_dtype="f32", Y=Y, workspace=wsb)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                mb.mdbf_forward(dl, X, y_dtype="f32", Y=Y, workspace=wsb)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            return {"ms_per_call": ms, "tokens_per_s": T / ms * 1e3,
+                    "dense_equivalent_TFLOPs": 2.0 * m * n * T / ms / 1e9,
+                    "issued_TFLOPs": 2.0 * (m + n) * k * (T + L) / ms / 1e9,
+                    "frac_fp16_mfma_peak": 2.0 * (m + n) * k * (T + L) / ms / 1e9 / 2500.0}
+
+        extras["decode_T16_mlp_gate"] = time_call(11008, 4096, 4096, 16, 300)
+        extras["prefill_T2048_attn"] = time_call(M, N, K, 2048, 300)
 
     out = {
         "metric": "MDBF decode GEMV HBM GB/s (% peak) + prefill TFLOP/s, LLaMA-7B shapes",

@@ -154,6 +154,13 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
 /* Runs all layers of a plan.  Asynchronous on `stream`, no allocation, no host-device copy. */
 int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream);
 
+/* Runs a part of a plan, for measuring its kernels one by one: `stages` and `kernels` are bit masks.
+ * stages: 1 = first factor (x -> z), 2 = second factor (z -> y).  kernels: 1 = the scale-in kernel of the
+ * stage (plans that have none skip it), 2 = the product kernel.  mdbf_forward_batch is (3, 3).  Results are
+ * only meaningful if the caller preserves the order scale-in -> product, stage 1 -> stage 2. */
+int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t plan_bytes, int stages,
+                            int kernels, void* stream);
+
 /* ---- misc ----------------------------------------------------------------------------- */
 const char* mdbf_strerror(int status);
 const char* mdbf_last_hip_error(void);   /* text of the last failed HIP call on this thread, or "" */

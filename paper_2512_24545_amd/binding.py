@@ -24,7 +24,7 @@ STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE",
 EXPORTS = [
     "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack",
     "mdbf_workspace_bytes", "mdbf_forward", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
-    "mdbf_forward_batch", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
+    "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
 ]
 
 
@@ -78,6 +78,7 @@ def lib():
     L.mdbf_batch_plan_bytes.argtypes = [C.c_int, C.POINTER(Layer), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     L.mdbf_batch_plan_build.argtypes = [C.c_int, C.POINTER(Layer), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]
     L.mdbf_forward_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.mdbf_forward_batch_part.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
     L.mdbf_strerror.restype = C.c_char_p
     L.mdbf_strerror.argtypes = [C.c_int]
     L.mdbf_last_hip_error.restype = C.c_char_p
@@ -239,5 +240,15 @@ class BatchPlan:
                                         _stream_ptr(stream)), "mdbf_forward_batch")
 
 
+    def run_part(self, stages, kernels, stream=None):
+        """One part of the plan (bit masks: stages 1|2, kernels 1 = scale-in, 2 = product)."""
+        _check(lib().mdbf_forward_batch_part(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), self.plan_bytes,
+                                             stages, kernels, _stream_ptr(stream)), "mdbf_forward_batch_part")
+
+
 def mdbf_forward_batch(plan, stream=None):
     plan.run(stream)
+
+
+def mdbf_forward_batch_part(plan, stages, kernels, stream=None):
+    plan.run_part(stages, kernels, stream)

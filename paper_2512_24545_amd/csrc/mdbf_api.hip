@@ -366,7 +366,13 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
 }
 
 int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream) {
+  return mdbf_forward_batch_part(plan_host, plan_dev, plan_bytes, 3, 3, stream);
+}
+
+int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t plan_bytes, int stages,
+                            int kernels, void* stream) {
   if (!plan_host || !plan_dev) return MDBF_EINVAL;
+  if (stages < 1 || stages > 3 || kernels < 1 || kernels > 3) return MDBF_EINVAL;
   if (!aligned16(plan_dev)) return MDBF_EALIGN;
   PlanHeader h;
   if (plan_bytes < sizeof(PlanHeader)) return MDBF_EWORKSPACE;
@@ -379,6 +385,7 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
     const unsigned char* host = (const unsigned char*)plan_host;
     for (int i = 0; i < h.count; ++i)
       for (int st = 0; st < 2; ++st) {
+        if (!(stages & (1 << st)) || !(kernels & 2)) continue;
         int e = launch_stage_gemm(nullptr, 0, 0, (const StageProb*)(host + h.probs_off[st]) + i, s);
         if (e) return hip_fail(e);
       }
@@ -386,6 +393,7 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
   }
   if (h.gemm) {
     for (int st = 0; st < 2; ++st) {
+      if (!(stages & (1 << st)) || !(kernels & 2)) continue;
       StageProb launch;
       memset(&launch, 0, sizeof(launch));
       launch.T = h.max_tokens;
@@ -400,23 +408,22 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
     StageProb dummy;
     memset(&dummy, 0, sizeof(dummy));
     dummy.ntiles = h.tiles_per_item[st];
-    int e;
-    if (h.precise)
-      e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
-    else if (h.mx[st]) {
-      e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
+    if (!(stages & (1 << st))) continue;
+    const bool pre_k = (kernels & 1) != 0, main_k = (kernels & 2) != 0;
+    int e = 0;
+    if (h.precise) {
+      if (main_k) e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
+    } else if (h.mx[st]) {
+      if (pre_k) e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
       if (e) return hip_fail(e);
-      e = launch_stage_mx(items, h.nitems[st], &dummy, s);
-    }
-    else if (h.fast[st]) {
-      if (h.pre[st]) {
-        e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);
-        if (e) return hip_fail(e);
-      }
-      e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item[st], &dummy, h.pre[st] != 0, s);
-    }
-    else
+      if (main_k) e = launch_stage_mx(items, h.nitems[st], &dummy, s);
+    } else if (h.fast[st]) {
+      if (h.pre[st] && pre_k) e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);
+      if (e) return hip_fail(e);
+      if (main_k) e = launch_stage_mfma(probs, items, h.nitems[st], h.tiles_per_item[st], &dummy, h.pre[st] != 0, s);
+    } else if (main_k) {
       e = launch_stage_generic(probs, items, h.nitems[st], h.tiles_per_item[st], &dummy, s);
+    }
     if (e) return hip_fail(e);
   }
   return MDBF_OK;
