@@ -12,7 +12,7 @@ reported, never as `value`: the product kernel timed by itself (the roofline obj
 layers issued as one mdbf_forward call each from a HIP graph, one layer re-run hot in cache, the
 latency of a single call, a 16-token call on an MLP projection, and the 2048-token prefill call.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (fields: see the README).
 """
 import argparse
 import json

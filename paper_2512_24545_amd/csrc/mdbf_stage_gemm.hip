@@ -31,9 +31,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 4;
-constexpr int kVinBufBytes = 128 * 256;     // 16 * TB <= 128 tokens x 128 columns fp16
 constexpr int kEinBufBytes = 128 * 32;      // 128 columns x 16 modes fp16
-constexpr int kSmemBytes = 2 * (kVinBufBytes + kEinBufBytes);
+// LDS of a workgroup with TB slabs of 16 tokens: two buffers of (16 TB tokens x 128 columns fp16) + envelope rows
+__host__ __device__ constexpr int vin_buf_bytes(int TB) { return 16 * TB * 256; }
+__host__ __device__ constexpr int smem_bytes(int TB) { return 2 * (vin_buf_bytes(TB) + kEinBufBytes); }
+// waves per SIMD the register budget is cut for: the small shapes live on occupancy (their blocks are short
+// dependent chains), the big one on registers
+__host__ __device__ constexpr int min_waves(int TB) { return TB >= 4 ? 2 : (TB == 2 ? 3 : 4); }
 
 __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
   half2v h;
@@ -93,8 +97,9 @@ __device__ __forceinline__ u32x4 load8_vec(const void* p, int64_t idx0) {
 // any types, ranks and alignments, element by element.
 // BATCH: the rows come from a plan's work items instead of the single problem.
 constexpr int kGeneric = 3;
+constexpr int kPlanR = 2;   // row tiles per wave in a plan's work items
 template <int R, int TB, int MODE, bool BATCH>
-__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(64 * kWaves, min_waves(TB))
 void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   // the rows of this workgroup: a work item of a plan (at most kWaves * R row tiles of one problem), or
@@ -112,6 +117,7 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
     item_end = min(item_tile0 + kWaves * R, p.ntiles);
   }
   unsigned char* vin_buf = smem;                               // [2][16*TB tokens][16 chunks of 16 B], swizzled
+  constexpr int kVinBufBytes = vin_buf_bytes(TB);
   unsigned char* ein_buf = smem + 2 * kVinBufBytes;            // [2][128 columns][16 modes]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -285,24 +291,28 @@ static int launch_rtmb(const WorkItem* items_dev, int nitems, const StageProb* p
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB, MODE, BATCH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(TB));
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
   const int rows_per_wg = kWaves * R;   // tiles
   const unsigned gx = BATCH ? (unsigned)nitems : (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
   const unsigned gy = (unsigned)((p->T + 16 * TB - 1) / (16 * TB));
-  hipLaunchKernelGGL((stage_gemm_kernel<R, TB, MODE, BATCH>), dim3(gx, gy), dim3(64 * kWaves), kSmemBytes, s,
+  hipLaunchKernelGGL((stage_gemm_kernel<R, TB, MODE, BATCH>), dim3(gx, gy), dim3(64 * kWaves), smem_bytes(TB), s,
                      items_dev, *p);
   return (int)hipGetLastError();
 }
 
-// plans exist for the one-tile-per-wave shapes only (R = 1)
 template <int R, int TB, int MODE>
 static int launch_rtm(const WorkItem* items_dev, int nitems, const StageProb* p, hipStream_t s) {
-  if (R == 1 && items_dev) return launch_rtmb<1, TB, MODE, true>(items_dev, nitems, p, s);
-  if (items_dev) return (int)hipErrorInvalidValue;
-  return launch_rtmb<R, TB, MODE, false>(nullptr, 0, p, s);
+  if (items_dev) {
+    // plans: items of kPlanR tiles per wave, short token slabs
+    if constexpr (R == kPlanR && TB <= 4) return launch_rtmb<R, TB, MODE, true>(items_dev, nitems, p, s);
+    return (int)hipErrorInvalidValue;
+  } else {
+    if constexpr (R == 1 || TB == 8) return launch_rtmb<R, TB, MODE, false>(nullptr, 0, p, s);
+    return (int)hipErrorInvalidValue;
+  }
 }
 
 template <int R, int TB>
@@ -330,15 +340,20 @@ int gemm_load_mode(const StageProb& p) {
   return fast ? p.vin_dt : gemm::kGeneric;
 }
 
-int gemm_tiles_per_item() { return gemm::kWaves; }
+int gemm_tiles_per_item() { return gemm::kWaves * gemm::kPlanR; }
 int gemm_plan_max_tokens() { return 64; }   // plans with longer problems launch the single-problem kernel per problem
 
 int launch_stage_gemm(const WorkItem* items_dev, int nitems, int mode, const StageProb* p, hipStream_t s) {
-  if (!items_dev) mode = gemm_load_mode(*p);
-  if (p->T > 64) return gemm::launch_rt<MDBF_GEMM_R, MDBF_GEMM_TB>(items_dev, nitems, mode, p, s);
-  if (p->T > 32) return gemm::launch_rt<1, 4>(items_dev, nitems, mode, p, s);
-  if (p->T > 16) return gemm::launch_rt<1, 2>(items_dev, nitems, mode, p, s);
-  return gemm::launch_rt<1, 1>(items_dev, nitems, mode, p, s);
+  if (items_dev) {
+    if (p->T > 32) return gemm::launch_rt<gemm::kPlanR, 4>(items_dev, nitems, mode, p, s);
+    if (p->T > 16) return gemm::launch_rt<gemm::kPlanR, 2>(items_dev, nitems, mode, p, s);
+    return gemm::launch_rt<gemm::kPlanR, 1>(items_dev, nitems, mode, p, s);
+  }
+  mode = gemm_load_mode(*p);
+  if (p->T > 64) return gemm::launch_rt<MDBF_GEMM_R, MDBF_GEMM_TB>(nullptr, 0, mode, p, s);
+  if (p->T > 32) return gemm::launch_rt<1, 4>(nullptr, 0, mode, p, s);
+  if (p->T > 16) return gemm::launch_rt<1, 2>(nullptr, 0, mode, p, s);
+  return gemm::launch_rt<1, 1>(nullptr, 0, mode, p, s);
 }
 
 }  // namespace mdbf
