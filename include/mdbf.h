@@ -54,6 +54,11 @@ typedef enum { MDBF_F16 = 0, MDBF_BF16 = 1, MDBF_F32 = 2 } mdbf_dtype;
 
 /* flags of mdbf_desc_t */
 #define MDBF_FLAG_PRECISE 1u   /* fp32 vector arithmetic throughout (no fp16 staging, no matrix cores); slow */
+#define MDBF_FLAG_ACCUMULATE 4u /* Y += What x instead of Y = What x: the terms of a residual stack
+                                   What = sum_p What^(p) with independent sign bases (paper Sec. 3.2,
+                                   "Residual Compensation", Eq. "dbf-residual-comp") are applied by one call each
+                                   on the same Y; the additions happen in the precision of Y.  Two terms of
+                                   one Y must not sit in the same plan: a plan's layers run in no defined order */
 #define MDBF_FLAG_BLOCK_SCALED 2u /* take the block-scaled matrix-core variant wherever it applies (l = 16, fp16
                                      envelopes, T <= 16), also for launches too small to fill the device with it;
                                      without the flag the library picks the variant by launch size */

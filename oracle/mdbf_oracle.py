@@ -153,6 +153,18 @@ def forward_factored(SA, SB, A, Q, G, B, X, return_intermediates=False):
     return Y
 
 
+def forward_residual_stack(terms, X):
+    """y = sum_p What^(p) x for a residual stack of independently factorised terms (the two-term form
+    of Eq. "dbf-residual-comp", any number of terms, each an MDBF factorisation with its own sign bases
+    and envelopes): the plain sum of the terms' products.  terms: sequence of (SA, SB, A, Q, G, B)."""
+    X = np.atleast_2d(_f64(X))
+    Y = None
+    for (SA, SB, A, Q, G, B) in terms:
+        Yp = forward_factored(SA, SB, A, Q, G, B, X)
+        Y = Yp if Y is None else Y + Yp
+    return Y
+
+
 def dbf_forward(SA, SB, a, mvec, b, X):
     """Plain DBF, y = D_a SA D_m SB D_b x, in the printed evaluation order of
     Eq. "DBF-inference-form" (scale, binary product, scale, binary product, scale),

@@ -16,6 +16,7 @@ from . import build as _build
 MDBF_F16, MDBF_BF16, MDBF_F32 = 0, 1, 2
 MDBF_FLAG_PRECISE = 1
 MDBF_FLAG_BLOCK_SCALED = 2
+MDBF_FLAG_ACCUMULATE = 4
 DTYPE_CODE = {"f16": MDBF_F16, "bf16": MDBF_BF16, "f32": MDBF_F32}
 
 STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE", -4: "MDBF_EWORKSPACE",
@@ -175,8 +176,9 @@ class DeviceLayer:
         env = [up(layer[kname]).to(dt).contiguous() for kname in ("A", "Q", "G", "B")]
         return DeviceLayer(layer["m"], layer["n"], layer["k"], layer["l"], SA, SB, *env)
 
-    def desc(self, x_dtype, y_dtype, precise=False, block_scaled=False):
-        flags = (MDBF_FLAG_PRECISE if precise else 0) | (MDBF_FLAG_BLOCK_SCALED if block_scaled else 0)
+    def desc(self, x_dtype, y_dtype, precise=False, block_scaled=False, accumulate=False):
+        flags = ((MDBF_FLAG_PRECISE if precise else 0) | (MDBF_FLAG_BLOCK_SCALED if block_scaled else 0) |
+                 (MDBF_FLAG_ACCUMULATE if accumulate else 0))
         return Desc(self.m, self.n, self.k, self.l, DTYPE_CODE[x_dtype], DTYPE_CODE[self.env_dtype],
                     DTYPE_CODE[y_dtype], flags)
 
@@ -190,12 +192,14 @@ def mdbf_workspace_bytes(desc, T):
     return out.value
 
 
-def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None, stream=None, block_scaled=False):
+def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None, stream=None, block_scaled=False,
+                 accumulate=False):
     """Y[b,:] = What X[b,:].  X: CUDA tensor (T, n) of f16/bf16/f32; returns Y (T, m) of y_dtype."""
     torch = _torch()
     assert X.is_cuda and X.dim() == 2 and X.shape[1] == layer.n and X.stride(1) == 1
     T = X.shape[0]
-    d = layer.desc(_dtype_name(X), y_dtype, precise, block_scaled)
+    d = layer.desc(_dtype_name(X), y_dtype, precise, block_scaled, accumulate)
+    assert not (accumulate and Y is None), "accumulate needs the Y to add to"
     if Y is None:
         Y = torch.empty((T, layer.m), dtype=_torch_dtype(y_dtype), device=X.device)
     if workspace is None:
@@ -210,13 +214,14 @@ def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None,
 class BatchPlan:
     """Plan for many independent layers: two launches for all of them."""
 
-    def __init__(self, layers, Xs, Ys, precise=False, block_scaled=False):
+    def __init__(self, layers, Xs, Ys, precise=False, block_scaled=False, accumulate=False):
         torch = _torch()
         assert len(layers) == len(Xs) == len(Ys) and len(layers) > 0
         n = len(layers)
         arr = (Layer * n)()
         for i, (L, X, Y) in enumerate(zip(layers, Xs, Ys)):
-            arr[i].desc = L.desc(_dtype_name(X), _dtype_name(Y), precise, block_scaled)
+            acc = accumulate[i] if isinstance(accumulate, (list, tuple)) else accumulate
+            arr[i].desc = L.desc(_dtype_name(X), _dtype_name(Y), precise, block_scaled, acc)
             arr[i].SA_packed_dev = L.SA_packed.data_ptr()
             arr[i].SB_packed_dev = L.SB_packed.data_ptr()
             arr[i].env = L.env()

@@ -30,7 +30,7 @@ int check_desc(const mdbf_desc_t* d) {
   if (d->m <= 0 || d->n <= 0 || d->k <= 0) return MDBF_EINVAL;
   if (d->l < 1 || d->l > MDBF_MAX_L) return MDBF_EINVAL;
   if (!valid_dtype(d->x_dtype) || !valid_dtype(d->env_dtype) || !valid_dtype(d->y_dtype)) return MDBF_EDTYPE;
-  if (d->flags & ~(MDBF_FLAG_PRECISE | MDBF_FLAG_BLOCK_SCALED)) return MDBF_EUNSUPPORTED;
+  if (d->flags & ~(MDBF_FLAG_PRECISE | MDBF_FLAG_BLOCK_SCALED | MDBF_FLAG_ACCUMULATE)) return MDBF_EUNSUPPORTED;
   return MDBF_OK;
 }
 
@@ -125,6 +125,7 @@ void make_stages(const mdbf_desc_t* d, const void* SA, const void* SB, const mdb
   s2.env_dt = d->env_dtype;
   s2.vin_dt = MDBF_F32;
   s2.out_dt = d->y_dtype;
+  s2.flags = (d->flags & MDBF_FLAG_ACCUMULATE) ? kStageAccumulate : 0;
   out[0] = s1;
   out[1] = s2;
 }

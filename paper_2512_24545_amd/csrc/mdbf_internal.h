@@ -73,8 +73,9 @@ struct StageProb {
   int32_t rows, K, l, T;
   int32_t KB, ntiles;
   int32_t env_dt, vin_dt, out_dt;
-  int32_t pad_;
+  int32_t flags;       // kStageAccumulate
 };
+constexpr int32_t kStageAccumulate = 1;   // out += result instead of out = result
 
 // A unit of work of the stage kernels: row tiles [tile0, tile0+ntiles) of problem `prob`, with a copy
 // of the problem so that one 128-byte read describes the whole item.
@@ -174,6 +175,11 @@ __device__ inline void store_from_float(void* p, int64_t idx, int dt, float v) {
   if (dt == MDBF_F32) ((float*)p)[idx] = v;
   else if (dt == MDBF_F16) ((_Float16*)p)[idx] = (_Float16)v;
   else ((uint16_t*)p)[idx] = float_to_bf16_rne(v);
+}
+// the store of a stage's result: plain, or added to what `p[idx]` holds (kStageAccumulate)
+__device__ inline void emit_result(void* p, int64_t idx, int dt, float v, int flags) {
+  if (flags & kStageAccumulate) v += load_as_float(p, idx, dt);
+  store_from_float(p, idx, dt, v);
 }
 __host__ __device__ inline int dtype_size(int dt) { return dt == MDBF_F32 ? 4 : 2; }
 

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(64) void stage_precise_kernel(const StageProb* __re
       a += __shfl_xor(a, 32);
       if (c < p.l && row < p.rows) o += a * load_as_float(p.Eout, (int64_t)row * p.l + c, p.env_dt);
     }
-    if (kg == 0 && row < p.rows) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, o);
+    if (kg == 0 && row < p.rows) emit_result(p.out, (int64_t)b * p.out_ld + row, p.out_dt, o, p.flags);
   }
 }
 

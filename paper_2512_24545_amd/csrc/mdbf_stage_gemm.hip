@@ -278,7 +278,7 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int b = tok0 + tb * 16 + 4 * g + i;
-          if (b < p.T) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, acc[tb][r][i]);
+          if (b < p.T) emit_result(p.out, (int64_t)b * p.out_ld + row, p.out_dt, acc[tb][r][i], p.flags);
         }
     }
   }

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void stage_generic_kernel(const StageProb* __r
           v += __shfl_xor(v, 2);
           v += __shfl_xor(v, 4);
           v += __shfl_xor(v, 8);
-          if (s == 0 && row < p.rows) store_from_float(p.out, (int64_t)b * p.out_ld + row, p.out_dt, v);
+          if (s == 0 && row < p.rows) emit_result(p.out, (int64_t)b * p.out_ld + row, p.out_dt, v, p.flags);
         }
       }
     }

@@ -327,7 +327,7 @@ __device__ __forceinline__ void make_unit(uint32_t desc, const StageProb& single
     u.p.env_dt = (int)d[22];
     u.p.vin_dt = (int)d[23];
     u.p.out_dt = (int)d[24];
-    u.p.pad_ = 0;
+    u.p.flags = (int)d[25];
     u.tile0 = (int)d[26];
     u.ntl = (int)d[27];
   } else {
@@ -553,7 +553,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
     for (int r = 0; r < R; ++r) {
       const int row = (u.tile0 + wave + 4 * r) * kTileRows + 4 * kg + n;
       if ((wave + 4 * r) < u.ntl && n < 4 && row < u.p.rows)
-        store_from_float(u.p.out, (int64_t)u.b * u.p.out_ld + row, u.p.out_dt, res[r]);
+        emit_result(u.p.out, (int64_t)u.b * u.p.out_ld + row, u.p.out_dt, res[r], u.p.flags);
     }
     DBG_T(41);
     if (!has_next) break;

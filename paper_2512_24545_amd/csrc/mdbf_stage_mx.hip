@@ -265,7 +265,7 @@ struct ItemInfo {
   const unsigned char* Eout;
   void* out;
   int64_t out_ld;
-  int rows, KB, T, out_dt;
+  int rows, KB, T, out_dt, flags;
   int tile0, ntl;
   int gt;                      // tiles in the packed layout's group that holds the item
 };
@@ -284,6 +284,7 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.KB = w.p.KB;
     it.T = w.p.T;
     it.out_dt = w.p.out_dt;
+    it.flags = w.p.flags;
     it.tile0 = w.tile0;
     it.ntl = w.ntiles;
     it.gt = group_tiles(w.tile0, w.p.ntiles);
@@ -297,6 +298,7 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.KB = single.KB;
     it.T = single.T;
     it.out_dt = single.out_dt;
+    it.flags = single.flags;
     it.tile0 = item * kItemTiles;
     it.ntl = min(kItemTiles, single.ntiles - it.tile0);
     it.gt = group_tiles(it.tile0, single.ntiles);
@@ -519,7 +521,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
             const int sel = n & 3;
             const float res = sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3];
             const int row = (it.tile0 + trel) * kTileRows + 4 * kg + n;
-            if (n < 4 && row < it.rows) store_from_float(it.out, (int64_t)b * it.out_ld + row, it.out_dt, res);
+            if (n < 4 && row < it.rows) emit_result(it.out, (int64_t)b * it.out_ld + row, it.out_dt, res, it.flags);
           }
         }
       }

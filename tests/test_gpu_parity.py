@@ -362,6 +362,44 @@ def test_many_token_batch(gpu):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
 
 
+# ---------------------------------------------------------------- residual stacks: Y += What x
+@pytest.mark.parametrize("T,y_dtype,variant", [(1, "f32", "auto"), (1, "f16", "auto"), (1, "f32", "block_scaled"),
+                                               (1, "f32", "precise"), (6, "f32", "auto"), (40, "bf16", "auto"),
+                                               (1, "f32", "generic")])
+def test_residual_stack_accumulates(gpu, T, y_dtype, variant):
+    """Two independently factorised terms applied to the same Y, the second with MDBF_FLAG_ACCUMULATE."""
+    torch, mb = gpu
+    m, n = 530, 2104
+    l = 5 if variant == "generic" else 16
+    terms = [synth.make_layer(m, n, k, l, seed=900 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+             for i, k in enumerate((1104, 520))]
+    X = synth.make_activations(n, T, seed=910, x_dtype="f16")
+    ref = orc.forward_residual_stack([_oracle_args(L) for L in terms], X)
+    Xd = _to_dev(torch, X, "f16")
+    kw = dict(precise=(variant == "precise"), block_scaled=(variant == "block_scaled"))
+    Y = mb.mdbf_forward(mb.DeviceLayer.from_host(terms[0]), Xd, y_dtype=y_dtype, **kw)
+    mb.mdbf_forward(mb.DeviceLayer.from_host(terms[1]), Xd, y_dtype=y_dtype, Y=Y, accumulate=True, **kw)
+    torch.cuda.synchronize()
+    slack = {"f32": 0.0, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}[y_dtype]   # two roundings to the output type
+    assert orc.max_rel_error(Y.float().cpu().numpy(), ref) <= TOL + slack
+
+
+def test_residual_stack_in_a_plan(gpu):
+    torch, mb = gpu
+    m, n = 272, 1032
+    terms = [synth.make_layer(m, n, k, 16, seed=920 + i, env_dtype="f16", env_kind="llama") for i, k in enumerate((4096, 1104))]
+    X = synth.make_activations(n, 1, seed=930, x_dtype="f16")
+    ref = orc.forward_residual_stack([_oracle_args(L) for L in terms], X)
+    Xd = _to_dev(torch, X, "f16")
+    Y = torch.zeros((1, m), dtype=torch.float32, device="cuda:0")
+    # the two terms of one output must not share a plan (their order is not defined inside one launch)
+    for i, L in enumerate(terms):
+        plan = mb.BatchPlan([mb.DeviceLayer.from_host(L)], [Xd], [Y], accumulate=(i > 0))
+        plan.run()
+    torch.cuda.synchronize()
+    assert orc.max_rel_error(Y.cpu().numpy(), ref) <= TOL
+
+
 # ---------------------------------------------------------------- the synthetic decoder stack
 @pytest.mark.parametrize("budget", ["1.0", "1.5", "2.0"])
 @pytest.mark.parametrize("T", [1, 8])

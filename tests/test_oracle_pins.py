@@ -240,3 +240,19 @@ def test_pins_detect_planted_mistakes(golden_tiny):
 def test_max_rel_error_definition():
     Y = np.array([[1.0, -4.0, 2.0]])
     assert orc.max_rel_error(Y + np.array([[0.0, 0.0, 0.02]]), Y) == pytest.approx(0.005)
+
+
+# ---- residual stacks (several independently factorised terms) ----
+def test_residual_stack_is_the_sum_of_dense_terms():
+    rng = np.random.default_rng(77)
+    m, n = 9, 11
+    terms, Wsum = [], np.zeros((m, n))
+    for (k, l) in ((5, 2), (7, 1), (3, 3)):
+        SA = synth.random_signs(rng, m, k); SB = synth.random_signs(rng, k, n)
+        A, Q, G, B = (rng.standard_normal((r, l)) for r in (m, k, k, n))
+        terms.append((SA, SB, A, Q, G, B))
+        Wsum += orc.dense_reconstruct(SA, SB, A, Q, G, B)
+    X = rng.standard_normal((4, n))
+    np.testing.assert_allclose(orc.forward_residual_stack(terms, X), X @ Wsum.T, rtol=1e-12, atol=1e-12)
+    # a planted mistake (a term dropped) is seen
+    assert not np.allclose(orc.forward_residual_stack(terms[:2], X), X @ Wsum.T)
