@@ -375,11 +375,7 @@ __device__ __forceinline__ void contract_block(const unsigned char* stage, int b
   for (int L = 0; L < 3; ++L) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-#ifdef MDBF_DBG_NOMFMA
-      acc[r][0] += __builtin_bit_cast(float, a[r][0] ^ a[r][1] ^ a[r][2] ^ a[r][3] ^ bl[L][0] ^ bl[L][3] ^ bl[L][5] ^ (int)sc);
-#else
       acc[r] = mx_mfma(a[r], bl[L], acc[r], L, sc);
-#endif
     }
   }
 }
@@ -493,11 +489,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
         slot = (slot + 1 == kStages) ? 0 : slot + 1;
 #pragma unroll
         for (int blk = 0; blk < SB; ++blk) {
-#ifdef MDBF_DBG_NOCOMPUTE
-          if (false) {
-#else
           if (t * SB + blk < it.KB) {
-#endif
             contract_block(stage, blk, lane, n, wave, acc, colsum);
           }
         }
