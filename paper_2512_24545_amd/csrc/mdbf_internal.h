@@ -4,6 +4,12 @@
 #include <stdint.h>
 #include "mdbf.h"
 
+// Every pointer the kernels receive is device global memory.  Saying so in the pointer type makes the
+// compiler emit global_* instead of flat_* accesses: a flat access also counts against the LDS counter, so
+// a wait for an LDS read would wait for every global load in flight as well.
+#define MDBF_GLOBAL __attribute__((address_space(1)))
+#define MDBF_LDS __attribute__((address_space(3)))
+
 namespace mdbf {
 
 // ---------------------------------------------------------------------------------------
@@ -160,9 +166,9 @@ int launch_stage_gemm(const WorkItem* items_dev, int nitems, int mode, const Sta
 
 // dtype helpers (device)
 __device__ inline float load_as_float(const void* p, int64_t idx, int dt) {
-  if (dt == MDBF_F32) return ((const float*)p)[idx];
-  if (dt == MDBF_F16) return (float)((const _Float16*)p)[idx];
-  uint32_t u = ((uint32_t)((const uint16_t*)p)[idx]) << 16;
+  if (dt == MDBF_F32) return ((const MDBF_GLOBAL float*)p)[idx];
+  if (dt == MDBF_F16) return (float)((const MDBF_GLOBAL _Float16*)p)[idx];
+  uint32_t u = ((uint32_t)((const MDBF_GLOBAL uint16_t*)p)[idx]) << 16;
   return __builtin_bit_cast(float, u);
 }
 __device__ inline uint16_t float_to_bf16_rne(float f) {
@@ -172,9 +178,9 @@ __device__ inline uint16_t float_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 __device__ inline void store_from_float(void* p, int64_t idx, int dt, float v) {
-  if (dt == MDBF_F32) ((float*)p)[idx] = v;
-  else if (dt == MDBF_F16) ((_Float16*)p)[idx] = (_Float16)v;
-  else ((uint16_t*)p)[idx] = float_to_bf16_rne(v);
+  if (dt == MDBF_F32) ((MDBF_GLOBAL float*)p)[idx] = v;
+  else if (dt == MDBF_F16) ((MDBF_GLOBAL _Float16*)p)[idx] = (_Float16)v;
+  else ((MDBF_GLOBAL uint16_t*)p)[idx] = float_to_bf16_rne(v);
 }
 // the store of a stage's result: plain, or added to what `p[idx]` holds (kStageAccumulate)
 __device__ inline void emit_result(void* p, int64_t idx, int dt, float v, int flags) {

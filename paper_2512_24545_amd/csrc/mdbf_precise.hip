@@ -35,7 +35,7 @@ __global__ __launch_bounds__(64) void stage_precise_kernel(const StageProb* __re
 #pragma unroll
     for (int c = 0; c < MDBF_MAX_L; ++c) acc[c] = 0.f;
     for (int q = 0; q < p.KB; ++q) {
-      const uint32_t w = p.S[word_offset(tile, q, lane, p.KB, p.ntiles)];
+      const uint32_t w = ((const MDBF_GLOBAL uint32_t*)p.S)[word_offset(tile, q, lane, p.KB, p.ntiles)];
       for (int bit = 0; bit < 32; ++bit) {
         const int col = q * kBlockCols + local_col_of_bit_p(bit, kg);
         if (col >= p.K) continue;

@@ -39,6 +39,13 @@ __host__ __device__ constexpr int smem_bytes(int TB) { return 2 * (vin_buf_bytes
 // dependent chains), the big one on registers
 __host__ __device__ constexpr int min_waves(int TB) { return TB >= 4 ? 2 : (TB == 2 ? 3 : 4); }
 
+// Envelope rows of a block in LDS: 128 columns x 16 modes fp16 (32 bytes a column).  A reconstruction
+// operand read touches columns 8a + b (+4), a, b = 0..3, eight bytes (four modes) per lane: in column order
+// the four values of `a` would land on the same banks.  Column bits 2 and 3 trade places in the row index,
+// and the 16-byte halves of a row trade places for columns with bit 4 set: the 32 lanes served together
+// then cover every bank once.
+__host__ __device__ constexpr int ein_row(int col) { return (col & ~12) | ((col & 4) << 1) | ((col & 8) >> 1); }
+
 __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
   half2v h;
   h.x = (_Float16)lo;
@@ -53,9 +60,9 @@ __device__ __forceinline__ u32x4 load8_as_half(const void* p, int64_t idx0, int 
   const int es = dtype_size(dt);
   const uintptr_t addr = (uintptr_t)p + (uintptr_t)idx0 * (uintptr_t)es;
   if (nvalid >= 8 && (addr & 15u) == 0) {
-    if (dt == MDBF_F16) return *reinterpret_cast<const u32x4*>(addr);
+    if (dt == MDBF_F16) return *(const MDBF_GLOBAL u32x4*)addr;
     if (dt == MDBF_BF16) {
-      const u32x4 raw = *reinterpret_cast<const u32x4*>(addr);
+      const u32x4 raw = *(const MDBF_GLOBAL u32x4*)addr;
       const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
       uint32_t o[4];
 #pragma unroll
@@ -63,8 +70,8 @@ __device__ __forceinline__ u32x4 load8_as_half(const void* p, int64_t idx0, int 
         o[i] = pack_half2(__builtin_bit_cast(float, w[i] << 16), __builtin_bit_cast(float, w[i] & 0xFFFF0000u));
       return u32x4{o[0], o[1], o[2], o[3]};
     }
-    const floatx4 a = *reinterpret_cast<const floatx4*>(addr);
-    const floatx4 b = *reinterpret_cast<const floatx4*>(addr + 16);
+    const floatx4 a = *(const MDBF_GLOBAL floatx4*)addr;
+    const floatx4 b = *(const MDBF_GLOBAL floatx4*)(addr + 16);
     return u32x4{pack_half2(a.x, a.y), pack_half2(a.z, a.w), pack_half2(b.x, b.y), pack_half2(b.z, b.w)};
   }
   float v[8];
@@ -76,9 +83,9 @@ __device__ __forceinline__ u32x4 load8_as_half(const void* p, int64_t idx0, int 
 // eight consecutive elements of known type, 16-byte aligned, no bounds to respect; fp16 pairs
 template <int DT>
 __device__ __forceinline__ u32x4 load8_vec(const void* p, int64_t idx0) {
-  if (DT == MDBF_F16) return reinterpret_cast<const u32x4*>((const _Float16*)p + idx0)[0];
+  if (DT == MDBF_F16) return ((const MDBF_GLOBAL u32x4*)((const _Float16*)p + idx0))[0];
   if (DT == MDBF_BF16) {
-    const u32x4 raw = reinterpret_cast<const u32x4*>((const uint16_t*)p + idx0)[0];
+    const u32x4 raw = ((const MDBF_GLOBAL u32x4*)((const uint16_t*)p + idx0))[0];
     const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
     uint32_t o[4];
 #pragma unroll
@@ -86,8 +93,8 @@ __device__ __forceinline__ u32x4 load8_vec(const void* p, int64_t idx0) {
       o[i] = pack_half2(__builtin_bit_cast(float, w[i] << 16), __builtin_bit_cast(float, w[i] & 0xFFFF0000u));
     return u32x4{o[0], o[1], o[2], o[3]};
   }
-  const floatx4 a = reinterpret_cast<const floatx4*>((const float*)p + idx0)[0];
-  const floatx4 b = reinterpret_cast<const floatx4*>((const float*)p + idx0)[1];
+  const floatx4 a = ((const MDBF_GLOBAL floatx4*)((const float*)p + idx0))[0];
+  const floatx4 b = ((const MDBF_GLOBAL floatx4*)((const float*)p + idx0))[1];
   return u32x4{pack_half2(a.x, a.y), pack_half2(a.z, a.w), pack_half2(b.x, b.y), pack_half2(b.z, b.w)};
 }
 
@@ -141,12 +148,12 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
     eo_op[r] = half4{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
   }
   // sign words: tiles past the end read the last tile (their rows are never stored)
-  const uint32_t* sbase[R];
+  const MDBF_GLOBAL uint32_t* sbase[R];
   size_t sstride[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int t = min(tile0 + r, item_end - 1);
-    sbase[r] = p.S + tile_base_words(t, KB) + lane;
+    sbase[r] = (const MDBF_GLOBAL uint32_t*)p.S + tile_base_words(t, KB) + lane;
     sstride[r] = (size_t)group_tiles(t, p.ntiles) * 64u;
   }
 
@@ -179,7 +186,7 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
     }
     if (MODE != kGeneric) {
       const int col = q * kBlockCols + (tid >> 1);
-      const u32x4 v = reinterpret_cast<const u32x4*>(p.Ein)[(size_t)min(col, p.K - 1) * 2 + (tid & 1)];
+      const u32x4 v = ((const MDBF_GLOBAL u32x4*)p.Ein)[(size_t)min(col, p.K - 1) * 2 + (tid & 1)];
       const bool ok = col < p.K;
       ein_reg = u32x4{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u};
     } else {
@@ -203,7 +210,8 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
       const int tok = id >> 4, c = id & 15;
       *reinterpret_cast<u32x4*>(vin_buf + buf * kVinBufBytes + tok * 256 + ((c ^ (tok & 15)) << 4)) = vin_reg[i];
     }
-    *reinterpret_cast<u32x4*>(ein_buf + buf * kEinBufBytes + (tid >> 1) * 32 + (tid & 1) * 16) = ein_reg;
+    *reinterpret_cast<u32x4*>(ein_buf + buf * kEinBufBytes + ein_row(tid >> 1) * 32 +
+                              (((tid & 1) ^ ((tid >> 5) & 1)) << 4)) = ein_reg;
   };
 
   fetch_block(0);
@@ -227,8 +235,9 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
     for (int f = 0; f < 4; ++f) {
       // A operands of the two reconstruction products: rows mi -> columns 32f + 8(mi/4) + mi%4 (+4)
       const int col0 = 32 * f + 8 * (r16 >> 2) + (r16 & 3);
-      const half4 ea0 = *reinterpret_cast<const half4*>(ein + col0 * 32 + g * 8);
-      const half4 ea1 = *reinterpret_cast<const half4*>(ein + (col0 + 4) * 32 + g * 8);
+      const int eoff = ein_row(col0) * 32 + ((g ^ ((r16 >> 2) & 2)) << 3);
+      const half4 ea0 = *reinterpret_cast<const half4*>(ein + eoff);
+      const half4 ea1 = *reinterpret_cast<const half4*>(ein + eoff + (ein_row(4) - ein_row(0)) * 32);
       half8 wop[R];
 #pragma unroll
       for (int r = 0; r < R; ++r) {

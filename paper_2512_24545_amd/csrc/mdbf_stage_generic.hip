@@ -74,16 +74,16 @@ __global__ __launch_bounds__(256) void stage_generic_kernel(const StageProb* __r
 
   // an item lies inside one group of tiles: one block stride for all its tiles
   const size_t bstride = (size_t)group_tiles(tile0, p.ntiles) * 64u;
-  const uint32_t* sbase[R];
+  const MDBF_GLOBAL uint32_t* sbase[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) sbase[r] = p.S + tile_base_words(min(tile0 + wave + 4 * r, p.ntiles - 1), KB);
+  for (int r = 0; r < R; ++r) sbase[r] = (const MDBF_GLOBAL uint32_t*)p.S + tile_base_words(min(tile0 + wave + 4 * r, p.ntiles - 1), KB);
 
   auto load_group = [&](int g, u32x4 (&w)[R]) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       u32x4 t = {0u, 0u, 0u, 0u};
       if (r < nt) {
-        const uint32_t* tb = sbase[r] + (size_t)(4 * g) * bstride + lane;
+        const MDBF_GLOBAL uint32_t* tb = sbase[r] + (size_t)(4 * g) * bstride + lane;
         t.x = tb[0];
         if (4 * g + 1 < KB) t.y = tb[bstride];
         if (4 * g + 2 < KB) t.z = tb[2 * bstride];

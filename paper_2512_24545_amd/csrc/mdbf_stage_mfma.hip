@@ -33,7 +33,6 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-#define MDBF_GLOBAL __attribute__((address_space(1)))
 typedef const MDBF_GLOBAL u32x4* g_u32x4_ptr;
 typedef const MDBF_GLOBAL uint32_t* g_u32_ptr;
 typedef const MDBF_GLOBAL floatx4* g_f32x4_ptr;

@@ -34,8 +34,6 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-#define MDBF_GLOBAL __attribute__((address_space(1)))
-#define MDBF_LDS __attribute__((address_space(3)))
 typedef const MDBF_GLOBAL u32x4* g_u32x4_ptr;
 typedef const MDBF_GLOBAL uint32_t* g_u32_ptr;
 typedef const MDBF_GLOBAL uint16_t* g_u16_ptr;
@@ -218,16 +216,16 @@ __global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const Stag
     a.x = limb[L][0]; a.y = limb[L][1]; a.z = limb[L][2]; a.w = limb[L][3];
     u32x2 bpart;
     bpart.x = limb[L][4]; bpart.y = limb[L][5];
-    reinterpret_cast<u32x4*>(blk + L * kLimbBytes)[lane] = a;
-    reinterpret_cast<u32x2*>(blk + L * kLimbBytes + 64 * 16)[lane] = bpart;
+    ((MDBF_GLOBAL u32x4*)(blk + L * kLimbBytes))[lane] = a;
+    ((MDBF_GLOBAL u32x2*)(blk + L * kLimbBytes + 64 * 16))[lane] = bpart;
   }
-  reinterpret_cast<uint32_t*>(blk + kScaleOff)[lane] =
+  ((MDBF_GLOBAL uint32_t*)(blk + kScaleOff))[lane] =
       (uint32_t)(E + 127) | ((uint32_t)(E + 123) << 8) | ((uint32_t)(E + 119) << 16);
 
   // ---- 3. column sums of the block
   part += __shfl_xor(part, 16);
   part += __shfl_xor(part, 32);
-  if (lane < 16) reinterpret_cast<float*>(blk + kColsumOff)[lane] = part;
+  if (lane < 16) ((MDBF_GLOBAL float*)(blk + kColsumOff))[lane] = part;
 }
 
 // ---------------------------------------------------------------------------------------------------
