@@ -130,6 +130,14 @@ void make_stages(const mdbf_desc_t* d, const void* SA, const void* SB, const mdb
   out[1] = s2;
 }
 
+// The many-token kernel rounds its activations to fp16 as it loads them.  When it runs both factors, the
+// first one stores z in fp16 right away: the same values reach the second product (one rounding, to nearest
+// even, either way), with half the bytes to move and no conversion on the way in.
+void half_intermediate(StageProb sp[2]) {
+  sp[0].out_dt = MDBF_F16;
+  sp[1].vin_dt = MDBF_F16;
+}
+
 }  // namespace
 
 extern "C" {
@@ -195,6 +203,12 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
   StageProb sp[2];
   make_stages(desc, SA_packed_dev, SB_packed_dev, env, X_dev, ldx, Y_dev, ldy, T, workspace_dev, sp);
   hipStream_t s = (hipStream_t)stream;
+  {
+    bool both_gemm = !(desc->flags & MDBF_FLAG_PRECISE) && T >= kGemmMinTokensSingle;
+    for (int i = 0; i < 2; ++i)
+      both_gemm = both_gemm && stage_is_gemm(sp[i]) && !((desc->flags & MDBF_FLAG_BLOCK_SCALED) && use_mx(sp[i]));
+    if (both_gemm) half_intermediate(sp);
+  }
   for (int i = 0; i < 2; ++i) {
     int e;
     const bool forced_mx = (desc->flags & MDBF_FLAG_BLOCK_SCALED) && use_mx(sp[i]);
@@ -328,6 +342,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
     StageProb sp[2];
     make_stages(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev, L->ldy, L->T,
                 (unsigned char*)workspace_dev + zoff, sp);
+    if (h.gemm) half_intermediate(sp);
     zoff += layer_ws_bytes(&L->desc, L->T);
     for (int s = 0; s < 2; ++s) {
       probs[s][i] = sp[s];

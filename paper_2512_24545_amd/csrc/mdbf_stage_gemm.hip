@@ -163,25 +163,44 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[tb][r] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  // ---- global -> register staging of one block: activations (TB/2 chunks... per thread) and envelope rows
+  // ---- staging of one block.  Envelope rows and sign words go through registers.  fp16 activations
+  //      (kDma) go from global memory straight into LDS, 16 bytes per lane and 1 KB (four token rows) per
+  //      instruction; the row swizzle is applied on the global side (a lane fetches the chunk that belongs at
+  //      its LDS slot).  Other types are converted in registers on the way.  Values past the end: tokens past
+  //      T are never stored; columns past K meet zeroed envelope rows (kDma) or are zeroed themselves.
+  constexpr bool kDma = (MODE == MDBF_F16);
   constexpr int kVinChunks = (16 * TB * 16) / (64 * kWaves);   // 16-byte chunks per thread: TB
-  u32x4 vin_reg[kVinChunks];
+  u32x4 vin_reg[kDma ? 1 : kVinChunks];
   u32x4 ein_reg;
   uint32_t sw_next[R];
-  auto fetch_block = [&](int q) {
+  auto dma_block = [&](int q, int buf) {
 #pragma unroll
     for (int i = 0; i < kVinChunks; ++i) {
       const int id = tid + 64 * kWaves * i;
-      const int tok = id >> 4, c = id & 15;
-      const int col = q * kBlockCols + c * 8;
-      const int b = tok0 + tok;
-      if (MODE == kGeneric) {
-        const int nvalid = (b < p.T) ? (p.K - col) : 0;
-        vin_reg[i] = load8_as_half(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + col, nvalid, p.vin_dt);
-      } else {
-        const u32x4 v = load8_vec<MODE>(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + min(col, p.K - 8));
-        const bool ok = (b < p.T) && (col < p.K);
-        vin_reg[i] = u32x4{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u};
+      const int tok = id >> 4, c = (id & 15) ^ (tok & 15);
+      const int col = min(q * kBlockCols + c * 8, p.K - 8);
+      const int b = min(tok0 + tok, p.T - 1);
+      const MDBF_GLOBAL _Float16* src = (const MDBF_GLOBAL _Float16*)p.vin + ((int64_t)b * p.vin_ld + col);
+      unsigned char* dst = vin_buf + buf * kVinBufBytes + (wave * 64 + 64 * kWaves * i) * 16;   // wave-uniform
+      __builtin_amdgcn_global_load_lds((const MDBF_GLOBAL void*)src, (MDBF_LDS void*)dst, 16, 0, 0);
+    }
+  };
+  auto fetch_block = [&](int q) {
+    if (!kDma) {
+#pragma unroll
+      for (int i = 0; i < kVinChunks; ++i) {
+        const int id = tid + 64 * kWaves * i;
+        const int tok = id >> 4, c = id & 15;
+        const int col = q * kBlockCols + c * 8;
+        const int b = tok0 + tok;
+        if (MODE == kGeneric) {
+          const int nvalid = (b < p.T) ? (p.K - col) : 0;
+          vin_reg[i] = load8_as_half(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + col, nvalid, p.vin_dt);
+        } else {
+          const u32x4 v = load8_vec<MODE>(p.vin, (int64_t)min(b, p.T - 1) * p.vin_ld + min(col, p.K - 8));
+          const bool ok = (b < p.T) && (col < p.K);
+          vin_reg[i] = u32x4{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u};
+        }
       }
     }
     if (MODE != kGeneric) {
@@ -204,27 +223,39 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
     for (int r = 0; r < R; ++r) sw_next[r] = sbase[r][(size_t)min(q, KB - 1) * sstride[r]];
   };
   auto stash_block = [&](int buf) {
+    if (!kDma) {
 #pragma unroll
-    for (int i = 0; i < kVinChunks; ++i) {
-      const int id = tid + 64 * kWaves * i;
-      const int tok = id >> 4, c = id & 15;
-      *reinterpret_cast<u32x4*>(vin_buf + buf * kVinBufBytes + tok * 256 + ((c ^ (tok & 15)) << 4)) = vin_reg[i];
+      for (int i = 0; i < kVinChunks; ++i) {
+        const int id = tid + 64 * kWaves * i;
+        const int tok = id >> 4, c = id & 15;
+        *reinterpret_cast<u32x4*>(vin_buf + buf * kVinBufBytes + tok * 256 + ((c ^ (tok & 15)) << 4)) = vin_reg[i];
+      }
     }
     *reinterpret_cast<u32x4*>(ein_buf + buf * kEinBufBytes + ein_row(tid >> 1) * 32 +
                               (((tid & 1) ^ ((tid >> 5) & 1)) << 4)) = ein_reg;
   };
 
+  // Register staging runs two blocks ahead (a block is requested at the end of one iteration and parked at
+  // the end of the next).  Direct staging runs one block ahead: block q + 1 is requested right after the
+  // barrier that opens iteration q, into the buffer iteration q - 1 has just released, and every wave waits
+  // for its own requests before it reaches the next barrier.
+  uint32_t sw[R];
+  if (kDma) dma_block(0, 0);
   fetch_block(0);
   stash_block(0);
-  uint32_t sw[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
-  fetch_block(min(1, KB - 1));
+  if (kDma) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else fetch_block(min(1, KB - 1));
 
 #pragma unroll 1
   for (int q = 0; q < KB; ++q) {
     const int cur = q & 1;
     __syncthreads();
+    if (kDma) {
+      dma_block(min(q + 1, KB - 1), cur ^ 1);
+      fetch_block(min(q + 1, KB - 1));
+    }
 
     // ---- per contraction step f (32 columns): rebuild the wave's pieces of W, wop[r] = B operand of the
     //      token product, then run the step over all token slabs.  The steps are independent of each other,
@@ -269,12 +300,13 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
           acc[tb][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[tb], wop[r], acc[tb][r], 0, 0, 0);
     }
 
-    // the block after this one was requested a whole iteration ago; park it and request the next
+    // park the next block's register-staged parts and (register staging) request the one after
     // (past the end the last block is requested again: no branch around the loads)
     stash_block(cur ^ 1);
 #pragma unroll
     for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
-    fetch_block(min(q + 2, KB - 1));
+    if (kDma) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else fetch_block(min(q + 2, KB - 1));
   }
 
   // ---- store: lane (r16, g) holds out[token 16 tb + 4g + i][row r16 of tile r]
@@ -319,7 +351,7 @@ static int launch_rtm(const WorkItem* items_dev, int nitems, const StageProb* p,
     if constexpr (R == kPlanR && TB <= 4) return launch_rtmb<R, TB, MODE, true>(items_dev, nitems, p, s);
     return (int)hipErrorInvalidValue;
   } else {
-    if constexpr (R == 1 || TB == 8) return launch_rtmb<R, TB, MODE, false>(nullptr, 0, p, s);
+    if constexpr (R == 1 || TB >= 6) return launch_rtmb<R, TB, MODE, false>(nullptr, 0, p, s);
     return (int)hipErrorInvalidValue;
   }
 }
@@ -334,12 +366,27 @@ static int launch_rt(const WorkItem* items_dev, int nitems, int mode, const Stag
 
 }  // namespace gemm
 
-#ifndef MDBF_GEMM_R
-#define MDBF_GEMM_R 2
-#endif
-#ifndef MDBF_GEMM_TB
-#define MDBF_GEMM_TB 8
-#endif
+// Token slabs per workgroup for a long single problem (two row tiles per wave).  A workgroup's cost per
+// column block is a fixed part (rebuilding its piece of the factor) plus a part per slab; the launch takes as
+// long as the busiest compute unit, which holds ceil(workgroups / units) of them.  Fewer slabs per workgroup
+// make more, lighter workgroups: worth it when that evens out the last round (166 row tiles x 2048 tokens:
+// 336 workgroups of 8 slabs leave most units with one workgroup and some with two; 462 of 6 slabs fill them).
+static int long_problem_slabs(const StageProb& p) {
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) == hipSuccess) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+  }
+  const int row_groups = (p.ntiles + 2 * gemm::kWaves - 1) / (2 * gemm::kWaves);
+  int best = 8;
+  double best_cost = 0.0;
+  for (int tb = 8; tb >= 6; --tb) {
+    const int64_t wgs = (int64_t)row_groups * ((p.T + 16 * tb - 1) / (16 * tb));
+    const double cost = (double)((wgs + cus - 1) / cus) * (4.8 + tb);   // fixed part ~ 4.8 slabs' worth
+    if (tb == 8 || cost < best_cost) { best = tb; best_cost = cost; }
+  }
+  return best;
+}
 bool stage_is_gemm(const StageProb& p) { return p.l >= 1 && p.l <= 16; }
 
 int gemm_load_mode(const StageProb& p) {
@@ -359,7 +406,13 @@ int launch_stage_gemm(const WorkItem* items_dev, int nitems, int mode, const Sta
     return gemm::launch_rt<gemm::kPlanR, 1>(items_dev, nitems, mode, p, s);
   }
   mode = gemm_load_mode(*p);
-  if (p->T > 64) return gemm::launch_rt<MDBF_GEMM_R, MDBF_GEMM_TB>(nullptr, 0, mode, p, s);
+  if (p->T > 64) {
+    switch (long_problem_slabs(*p)) {
+      case 6: return gemm::launch_rt<2, 6>(nullptr, 0, mode, p, s);
+      case 7: return gemm::launch_rt<2, 7>(nullptr, 0, mode, p, s);
+      default: return gemm::launch_rt<2, 8>(nullptr, 0, mode, p, s);
+    }
+  }
   if (p->T > 32) return gemm::launch_rt<1, 4>(nullptr, 0, mode, p, s);
   if (p->T > 16) return gemm::launch_rt<1, 2>(nullptr, 0, mode, p, s);
   return gemm::launch_rt<1, 1>(nullptr, 0, mode, p, s);
