@@ -31,6 +31,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 4;
+constexpr int kDies = 8;                    // accelerator dies (XCDs); workgroup i is placed on die i mod 8
 constexpr int kEinBufBytes = 128 * 32;      // 128 columns x 16 modes fp16
 // LDS of a workgroup with TB slabs of 16 tokens: two buffers of (16 TB tokens x 128 columns fp16) + envelope rows
 __host__ __device__ constexpr int vin_buf_bytes(int TB) { return 16 * TB * 256; }
@@ -112,15 +113,26 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
   // the rows of this workgroup: a work item of a plan (at most kWaves * R row tiles of one problem), or
   // the blockIdx.x-th run of kWaves * R tiles of the single problem
   StageProb p;
-  int item_tile0, item_end;
+  int item_tile0, item_end, slab_group;
   if (BATCH) {
     const WorkItem& w = items[blockIdx.x];   // uniform address: scalar loads
     p = w.p;
     item_tile0 = w.tile0;
     item_end = w.tile0 + w.ntiles;
+    slab_group = blockIdx.y;
   } else {
+    // One-dimensional grid.  Workgroups go to the chip's eight dies in turn (id mod 8), each die with an L2
+    // of its own; the (token slab group, row group) pairs, token-major, are dealt out in eight contiguous
+    // runs, one per die: the workgroups that read the same activations share an L2.
     p = single;
-    item_tile0 = blockIdx.x * (kWaves * R);
+    const int row_groups = (p.ntiles + kWaves * R - 1) / (kWaves * R);
+    const int slab_groups = (p.T + 16 * TB - 1) / (16 * TB);
+    const int total = row_groups * slab_groups;
+    const int per_die = (total + kDies - 1) / kDies;
+    const int unit = (blockIdx.x % kDies) * per_die + blockIdx.x / kDies;
+    if (unit >= total) return;
+    slab_group = unit / row_groups;
+    item_tile0 = (unit - slab_group * row_groups) * (kWaves * R);
     item_end = min(item_tile0 + kWaves * R, p.ntiles);
   }
   unsigned char* vin_buf = smem;                               // [2][16*TB tokens][16 chunks of 16 B], swizzled
@@ -130,7 +142,7 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r16 = lane & 15, g = lane >> 4;
   const int tile0 = item_tile0 + wave * R;                     // first row tile of this wave
-  const int tok0 = blockIdx.y * (16 * TB);
+  const int tok0 = slab_group * (16 * TB);
   if (tok0 >= p.T) return;                                     // a plan's grid covers its longest problem
   const int KB = p.KB;
 
@@ -337,8 +349,13 @@ static int launch_rtmb(const WorkItem* items_dev, int nitems, const StageProb* p
     attr_set = true;
   }
   const int rows_per_wg = kWaves * R;   // tiles
-  const unsigned gx = BATCH ? (unsigned)nitems : (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
-  const unsigned gy = (unsigned)((p->T + 16 * TB - 1) / (16 * TB));
+  unsigned gx = BATCH ? (unsigned)nitems : (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
+  unsigned gy = (unsigned)((p->T + 16 * TB - 1) / (16 * TB));
+  if (!BATCH) {
+    const unsigned total = gx * gy;
+    gx = kDies * ((total + kDies - 1) / kDies);
+    gy = 1;
+  }
   hipLaunchKernelGGL((stage_gemm_kernel<R, TB, MODE, BATCH>), dim3(gx, gy), dim3(64 * kWaves), smem_bytes(TB), s,
                      items_dev, *p);
   return (int)hipGetLastError();
