@@ -74,6 +74,15 @@ def make_layer(m, n, k, l, seed, env_dtype="f16", env_kind="llama", signed_env=F
     return dict(m=m, n=n, k=k, l=l, SA=SA, SB=SB, A=A, Q=Q, G=G, B=B, env_dtype=env_dtype)
 
 
+def structured_weight(rows, cols, seed, decay=0.7, scale=0.02):
+    """A dense weight matrix with a decaying spectrum (singular values ~ i^-decay), the input of a
+    quantisation run: Gaussian factors around a power-law diagonal, scaled to weight-like magnitudes."""
+    rng = np.random.default_rng(seed)
+    r = min(rows, cols)
+    core = rng.standard_normal((rows, r)) @ np.diag(1.0 / np.arange(1, r + 1) ** decay) @ rng.standard_normal((r, cols))
+    return scale * core / np.sqrt(r)
+
+
 def make_activations(n, T, seed, x_dtype="f16", kind="normal"):
     """kind "normal": N(0,1);  "ternary": i.i.d. from {-1,0,+1} (exact-integer tests)."""
     rng = np.random.default_rng(seed)

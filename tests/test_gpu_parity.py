@@ -422,3 +422,27 @@ def test_decoder_stack_layer_through_batch(gpu, budget, T):
     torch.cuda.synchronize()
     for Yb, ref in zip(Ys, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
+
+
+# ---------------------------------------------------------------- factors with the structure of a quantisation run
+@pytest.mark.parametrize("rows,cols,R,l,outer", [(320, 288, 96, 4, 1), (272, 400, 160, 16, 0), (272, 400, 160, 16, 2)])
+@pytest.mark.parametrize("variant", ["auto", "block_scaled", "tokens", "precise"])
+def test_quantized_structured_factors(gpu, rows, cols, R, l, outer, variant):
+    """The layer comes from the quantizer oracle run on a dense matrix with a decaying spectrum: sign masks
+    correlated with the weights, envelope modes of mixed sign and falling size (the i.i.d. factors of the
+    benchmark configurations have neither)."""
+    from oracle import mdbf_quantizer as qz
+    if variant == "block_scaled" and l != 16:
+        pytest.skip("the block-scaled kernel takes rank-16 envelopes")
+    W = synth.structured_weight(rows, cols, seed=rows + cols + l)
+    L = qz.quantize(W, R, l, outer=outer)
+    for key in ("A", "Q", "G", "B"):
+        L[key] = synth.round_to_dtype(L[key], "f16")
+    L["env_dtype"] = "f16"
+    T = 5 if variant == "tokens" else 1
+    X = synth.make_activations(cols, T, seed=77 + outer, x_dtype="f16")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, "f16", "f32", precise=(variant == "precise"), block_scaled=(variant == "block_scaled"))
+    assert orc.max_rel_error(got, ref) <= (TOL_PRECISE if variant == "precise" else TOL)
+    # the layer does stand for W: its product is far closer to W x than W x is to zero
+    assert orc.max_rel_error(ref, X.astype(np.float64) @ W.T) < 0.9
