@@ -112,7 +112,8 @@ int mdbf_unpack(const void* packed_dev, int rows, int cols,
                 int8_t* signs_dev, int64_t ld, void* stream);
 
 /* ---- forward product ------------------------------------------------------------------
- * Workspace bytes needed by mdbf_forward for T tokens (holds the inner vector z, fp32). */
+ * Workspace bytes needed by mdbf_forward for T tokens (room for the inner vector z in fp32, and for the
+ * scaled activations of few-token calls). */
 int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out);
 
 /* Y[b,:] = What X[b,:] for b < T.
@@ -120,12 +121,13 @@ int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out);
  *   X_dev  T x n row-major, leading dimension ldx >= n (elements of x_dtype)
  *   Y_dev  T x m row-major, leading dimension ldy >= m (elements of y_dtype); overwritten
  *   workspace_dev / workspace_bytes  caller-owned scratch, >= mdbf_workspace_bytes()
- * Default arithmetic: fp32 accumulation on the matrix cores, z kept in fp32.  One token: the l-way
+ * Default arithmetic: fp32 accumulation on the matrix cores.  One token: z kept in fp32; the l-way
  * scaled activations (b^(s) o x and q^(t) o z) are quantised once -- to fp16, or, in the block-scaled
  * variant the library takes for large plans, to three fp6 limbs under a shared power-of-two scale per 32
  * values (about 13 bits) -- and contracted with the sign words.  Two tokens or more: the factors
  * S_A o (A Q^T), S_B o (G B^T) are rebuilt piece by piece in fp16 and applied as dense products to the
- * fp16-rounded activations.  Magnitudes above 65504 in those fp16 quantities overflow.
+ * fp16-rounded activations (x and z; z is stored in fp16 between the two products).  Magnitudes above
+ * 65504 in those fp16 quantities overflow.
  * With MDBF_FLAG_PRECISE everything is fp32 vector arithmetic. */
 int mdbf_forward(const mdbf_desc_t* desc,
                  const void* SA_packed_dev, const void* SB_packed_dev,
