@@ -446,3 +446,16 @@ def test_quantized_structured_factors(gpu, rows, cols, R, l, outer, variant):
     assert orc.max_rel_error(got, ref) <= (TOL_PRECISE if variant == "precise" else TOL)
     # the layer does stand for W: its product is far closer to W x than W x is to zero
     assert orc.max_rel_error(ref, X.astype(np.float64) @ W.T) < 0.9
+
+
+# ---------------------------------------------------------------- a tall, ragged projection (vocabulary-sized)
+@pytest.mark.parametrize("T,variant", [(1, "auto"), (1, "block_scaled"), (3, "auto"), (70, "auto")])
+def test_tall_ragged_projection(gpu, T, variant):
+    """m = 32003 rows (2001 row tiles: 31 full groups of the packed layout and a ragged one), k = 1000
+    (not a multiple of 128).  Every output is checked: the factored oracle is cheap at this shape."""
+    L = synth.make_layer(32003, 1536, 1000, 16, seed=321, env_dtype="f16", env_kind="llama", signed_env=True)
+    X = synth.make_activations(1536, T, seed=322, x_dtype="f16")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, "f16", "f32", block_scaled=(variant == "block_scaled"))
+    assert got.shape == (T, 32003)
+    assert orc.max_rel_error(got, ref) <= TOL
