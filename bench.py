@@ -171,10 +171,18 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f)["hbm_bytes_per_layer_per_launch"] * a.copies
-    roof = {"bound": "hbm", "kernel": "stage_mx_kernel", "achieved": (bytes_step / 2) / avg_launch_ms / 1e6,
+    # the share of a layer's algorithmic bytes that the product kernel itself moves, averaged over its two
+    # launches per step: the packed signs of the factor, the envelope factor on its output side (G resp. A)
+    # and y; the other envelope factor (B resp. Q) and x are read by the scale-in kernel
+    product_bytes_layer = ((M + N) * K // 8 + 2 * L * (K + M) + 2 * M) / 2
+    scale_in_bytes_layer = (2 * L * (N + K) + 2 * N) / 2
+    assert 2 * (product_bytes_layer + scale_in_bytes_layer) == algorithmic_bytes(M, N, K, L)
+    bytes_launch = product_bytes_layer * a.copies
+    roof = {"bound": "hbm", "kernel": "stage_mx_kernel", "achieved": bytes_launch / avg_launch_ms / 1e6,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": traffic,
-            "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_step / 2,
-            "scale_in_avg_launch_us": avg_scale_in_ms * 1e3}
+            "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_launch,
+            "scale_in_avg_launch_us": avg_scale_in_ms * 1e3,
+            "scale_in_algorithmic_bytes_per_launch": scale_in_bytes_layer * a.copies}
     roof["frac"] = roof["achieved"] / roof["peak"]
 
     extras = {}
