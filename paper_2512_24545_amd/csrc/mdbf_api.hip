@@ -140,6 +140,19 @@ void half_intermediate(StageProb sp[2]) {
 
 }  // namespace
 
+int mdbf::compute_units() {
+  static int cached = 0;
+  if (!cached) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      cached = cus;
+    else
+      cached = 256;
+  }
+  return cached;
+}
+
 extern "C" {
 
 double mdbf_bpw(int m, int n, int k, int l, int env_bits, int merge_inner) {

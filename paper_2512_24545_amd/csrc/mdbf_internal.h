@@ -158,6 +158,8 @@ bool stage_is_gemm(const StageProb& p);
 // how the kernel may load the problem's operands: a dtype code (vector loads of that activation type, fp16
 // rank-16 envelopes, aligned rows) or 3 (element by element); a plan takes 3 unless all problems agree
 int gemm_load_mode(const StageProb& p);
+// compute units of the current device (cached after the first call; 256 if the query fails)
+int compute_units();
 int gemm_tiles_per_item();
 int gemm_plan_max_tokens();
 // items_dev null: the single problem *p (mode ignored).  Else the work items of a plan (at most

@@ -389,11 +389,7 @@ static int launch_rt(const WorkItem* items_dev, int nitems, int mode, const Stag
 // make more, lighter workgroups: worth it when that evens out the last round (166 row tiles x 2048 tokens:
 // 336 workgroups of 8 slabs leave most units with one workgroup and some with two; 462 of 6 slabs fill them).
 static int long_problem_slabs(const StageProb& p) {
-  int dev = 0, cus = 256;
-  if (hipGetDevice(&dev) == hipSuccess) {
-    int v = 0;
-    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-  }
+  const int cus = compute_units();
   const int row_groups = (p.ntiles + 2 * gemm::kWaves - 1) / (2 * gemm::kWaves);
   int best = 8;
   double best_cost = 0.0;

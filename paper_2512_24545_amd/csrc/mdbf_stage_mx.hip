@@ -522,18 +522,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   }
 }
 
-static int max_workgroups() {
-  static int max_wgs = 0;
-  if (!max_wgs) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      max_wgs = kWgsPerCu * cus;
-    else
-      max_wgs = kWgsPerCu * 256;
-  }
-  return max_wgs;
-}
+static int max_workgroups() { return kWgsPerCu * compute_units(); }
 
 template <bool BATCH>
 static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
