@@ -459,3 +459,22 @@ def test_tall_ragged_projection(gpu, T, variant):
     got = _run(gpu, L, X, "f16", "f32", block_scaled=(variant == "block_scaled"))
     assert got.shape == (T, 32003)
     assert orc.max_rel_error(got, ref) <= TOL
+
+
+def test_sibling_projections_share_their_input(gpu):
+    """q, k, v (and gate, up) of a decoder layer read the same activations: three layers of one plan point
+    at one X buffer; each result equals the oracle's for that layer."""
+    torch, mb = gpu
+    X = synth.make_activations(1024, 1, seed=901, x_dtype="f16")
+    Xd = _to_dev(torch, X, "f16")
+    layers, Ys, refs = [], [], []
+    for i, (m, k) in enumerate([(1024, 640), (1024, 640), (512, 384)]):
+        L = synth.make_layer(m, 1024, k, 16, seed=910 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+        layers.append(mb.DeviceLayer.from_host(L))
+        Ys.append(torch.zeros((1, m), dtype=torch.float32, device="cuda:0"))
+        refs.append(orc.forward_factored(*_oracle_args(L), X))
+    plan = mb.BatchPlan(layers, [Xd, Xd, Xd], Ys)
+    plan.run()
+    torch.cuda.synchronize()
+    for Yb, ref in zip(Ys, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
