@@ -111,6 +111,14 @@ int mdbf_pack(const int8_t* signs_dev, int rows, int cols, int64_t ld,
 int mdbf_unpack(const void* packed_dev, int rows, int cols,
                 int8_t* signs_dev, int64_t ld, void* stream);
 
+/* Envelope factor with zero modes appended (offline, like mdbf_pack): out_dev (rows x l_to, row-major)
+ * receives env_dev (rows x l, row-major, elements of `dtype`) in its first l columns and zeros in the rest.
+ * A layer whose four envelope factors are padded this way and whose descriptor says l_to denotes the same
+ * What (paper Eq. "me-dbf-basis": the added modes are zero terms of the rank-l sums); ranks 8 and 16 with fp16
+ * envelopes are the ones the matrix-core decode kernels serve, other ranks run the slower generic kernel.
+ * l_to >= l, l_to <= MDBF_MAX_L; both pointers 16-byte aligned; the buffers must not overlap. */
+int mdbf_pad_envelope(const void* env_dev, int rows, int l, int dtype, void* out_dev, int l_to, void* stream);
+
 /* ---- forward product ------------------------------------------------------------------
  * Workspace bytes needed by mdbf_forward for T tokens (room for the inner vector z in fp32, and for the
  * scaled activations of few-token calls). */

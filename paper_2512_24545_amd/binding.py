@@ -23,7 +23,7 @@ STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE",
           -5: "MDBF_EUNSUPPORTED", -6: "MDBF_EHIP"}
 
 EXPORTS = [
-    "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack",
+    "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack", "mdbf_pad_envelope",
     "mdbf_workspace_bytes", "mdbf_forward", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
     "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
 ]
@@ -73,6 +73,7 @@ def lib():
     L.mdbf_packed_bytes.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     L.mdbf_pack.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
     L.mdbf_unpack.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+    L.mdbf_pad_envelope.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
     L.mdbf_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int, C.POINTER(C.c_size_t)]
     L.mdbf_forward.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.POINTER(Env), C.c_void_p, C.c_int64,
                                C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -156,6 +157,16 @@ def mdbf_unpack(packed, rows, cols, stream=None):
     return out
 
 
+def mdbf_pad_envelope(env, l_to, stream=None):
+    """env: CUDA tensor (rows, l), contiguous.  Returns (rows, l_to) with zero modes appended."""
+    torch = _torch()
+    assert env.is_cuda and env.dim() == 2 and env.is_contiguous()
+    out = torch.empty((env.shape[0], l_to), dtype=env.dtype, device=env.device)
+    _check(lib().mdbf_pad_envelope(env.data_ptr(), env.shape[0], env.shape[1], DTYPE_CODE[_dtype_name(env)],
+                                   out.data_ptr(), l_to, _stream_ptr(stream)), "mdbf_pad_envelope")
+    return out
+
+
 class DeviceLayer:
     """Device-resident MDBF layer: packed sign bases and envelope factors."""
 
@@ -175,6 +186,11 @@ class DeviceLayer:
         SB = mdbf_pack(up(layer["SB"]))
         env = [up(layer[kname]).to(dt).contiguous() for kname in ("A", "Q", "G", "B")]
         return DeviceLayer(layer["m"], layer["n"], layer["k"], layer["l"], SA, SB, *env)
+
+    def padded(self, l_to):
+        """The same layer with envelope rank l_to >= l (zero modes appended through mdbf_pad_envelope)."""
+        env = [mdbf_pad_envelope(e, l_to) for e in (self.A, self.Q, self.G, self.B)]
+        return DeviceLayer(self.m, self.n, self.k, l_to, self.SA_packed, self.SB_packed, *env)
 
     def desc(self, x_dtype, y_dtype, precise=False, block_scaled=False, accumulate=False):
         flags = ((MDBF_FLAG_PRECISE if precise else 0) | (MDBF_FLAG_BLOCK_SCALED if block_scaled else 0) |

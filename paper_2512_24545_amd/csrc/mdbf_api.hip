@@ -37,9 +37,10 @@ int check_desc(const mdbf_desc_t* d) {
 size_t z_bytes(const mdbf_desc_t* d, int T) { return align_up((size_t)T * (size_t)kpad_of(d->k) * 4u, 256); }
 
 // Buffers for the pre-scaled activations of the two stages (only for small token counts and the
-// l = 16 / fp16-envelope case the matrix-core kernel serves; zero otherwise).
+// fp16-envelope cases of rank 16 or 8 the matrix-core kernels serve; zero otherwise).
 bool wants_xs(const mdbf_desc_t* d, int T) {
-  return T <= kMaxPreTokens && d->l == 16 && d->env_dtype == MDBF_F16 && !(d->flags & MDBF_FLAG_PRECISE);
+  return T <= kMaxPreTokens && (d->l == 16 || d->l == 8) && d->env_dtype == MDBF_F16 &&
+         !(d->flags & MDBF_FLAG_PRECISE);
 }
 size_t xs_need(int K, int T) {
   const size_t a = xs_bytes_for(K, T), b = xs_bytes_for_mx(K, T);
@@ -195,6 +196,13 @@ int mdbf_unpack(const void* packed_dev, int rows, int cols, int8_t* signs_dev, i
   if (!signs_dev || !packed_dev || rows <= 0 || cols <= 0 || ld < cols) return MDBF_EINVAL;
   if (!aligned16(packed_dev)) return MDBF_EALIGN;
   return hip_fail(launch_unpack((const uint32_t*)packed_dev, rows, cols, signs_dev, ld, (hipStream_t)stream));
+}
+
+int mdbf_pad_envelope(const void* env_dev, int rows, int l, int dtype, void* out_dev, int l_to, void* stream) {
+  if (!env_dev || !out_dev || rows <= 0 || l < 1 || l_to < l || l_to > MDBF_MAX_L) return MDBF_EINVAL;
+  if (!valid_dtype(dtype)) return MDBF_EDTYPE;
+  if (!aligned16(env_dev) || !aligned16(out_dev)) return MDBF_EALIGN;
+  return hip_fail(launch_pad_envelope(env_dev, rows, l, out_dev, l_to, dtype_size(dtype), (hipStream_t)stream));
 }
 
 int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out) {

@@ -116,6 +116,7 @@ constexpr uint32_t kPlanMagic = 0x4D444246u;  // "MDBF"
 // launchers (defined in the kernel translation units); return hipError_t as int
 int launch_pack(const int8_t* signs, int rows, int cols, int64_t ld, uint32_t* packed, hipStream_t s);
 int launch_unpack(const uint32_t* packed, int rows, int cols, int8_t* signs, int64_t ld, hipStream_t s);
+int launch_pad_envelope(const void* src, int rows, int l, void* dst, int l_to, int es, hipStream_t s);
 int launch_stage_precise(const StageProb* probs_dev, const WorkItem* items_dev, int nitems,
                          const StageProb* single, hipStream_t s);
 // pre: the problems' xs buffers hold the pre-scaled activations (launch_scale_in ran before)
@@ -133,7 +134,7 @@ size_t xs_bytes_for(int K, int T);
 size_t xs_bytes_for_mx(int K, int T);
 int mx_item_tiles();                         // row tiles per work item of this variant
 int mx_max_workgroups();                     // workgroups of this variant the current device holds at once
-bool stage_is_mx(const StageProb& p);        // l == 16, fp16 envelopes, an xs buffer, few tokens
+bool stage_is_mx(const StageProb& p);        // l == 16 or 8, fp16 envelopes, an xs buffer, few tokens
 // max_units: largest tokens x blocks of a problem of the launch
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single,
                        hipStream_t s);

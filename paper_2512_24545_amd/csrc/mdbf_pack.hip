@@ -60,4 +60,27 @@ int launch_unpack(const uint32_t* packed, int rows, int cols, int8_t* signs, int
   return (int)hipGetLastError();
 }
 
+// Envelope factor with zero modes appended: dst[r, c] = src[r, c] for c < l, 0 for l <= c < l_to.
+// The product is unchanged (the extra modes contribute nothing); ranks 8 and 16 are the ones the matrix-core
+// kernels take.  Elements are moved as raw bits: es = bytes per element (2 or 4).
+__global__ __launch_bounds__(256) void pad_envelope_kernel(const unsigned char* __restrict__ src, int rows, int l,
+                                                           unsigned char* __restrict__ dst, int l_to, int es) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)rows * (size_t)l_to) return;
+  const size_t r = i / (size_t)l_to;
+  const int c = (int)(i - r * (size_t)l_to);
+  if (es == 2) {
+    ((MDBF_GLOBAL uint16_t*)dst)[i] = c < l ? ((const MDBF_GLOBAL uint16_t*)src)[r * (size_t)l + c] : (uint16_t)0;
+  } else {
+    ((MDBF_GLOBAL uint32_t*)dst)[i] = c < l ? ((const MDBF_GLOBAL uint32_t*)src)[r * (size_t)l + c] : 0u;
+  }
+}
+
+int launch_pad_envelope(const void* src, int rows, int l, void* dst, int l_to, int es, hipStream_t s) {
+  const size_t n = (size_t)rows * (size_t)l_to;
+  hipLaunchKernelGGL(pad_envelope_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                     (const unsigned char*)src, rows, l, (unsigned char*)dst, l_to, es);
+  return (int)hipGetLastError();
+}
+
 }  // namespace mdbf

@@ -100,7 +100,7 @@ __device__ __forceinline__ u32x4 load8_vec(const void* p, int64_t idx0) {
 }
 
 // R row tiles per wave, TB slabs of 16 tokens per workgroup.  MODE 0..2: the common case -- fp16 envelopes of
-// rank 16, activations of type MODE with 16-byte aligned rows and K a multiple of 8: every load is a full
+// rank 16 or 8, activations of type MODE with 16-byte aligned rows and K a multiple of 8: every load is a full
 // vector, issued without a branch (addresses are clamped, values past the end replaced by zero).  MODE 3:
 // any types, ranks and alignments, element by element.
 // BATCH: the rows come from a plan's work items instead of the single problem.
@@ -217,8 +217,11 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
     }
     if (MODE != kGeneric) {
       const int col = q * kBlockCols + (tid >> 1);
-      const u32x4 v = ((const MDBF_GLOBAL u32x4*)p.Ein)[(size_t)min(col, p.K - 1) * 2 + (tid & 1)];
-      const bool ok = col < p.K;
+      // rank 8: a row is one 16-byte vector; the half that would hold modes 8..15 becomes zero
+      const int hl = p.l >> 3;
+      const bool has_modes = (tid & 1) < hl;
+      const u32x4 v = ((const MDBF_GLOBAL u32x4*)p.Ein)[(size_t)min(col, p.K - 1) * hl + (has_modes ? (tid & 1) : 0)];
+      const bool ok = (col < p.K) && has_modes;
       ein_reg = u32x4{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u};
     } else {
       const int colr = tid >> 1, half = tid & 1;
@@ -404,7 +407,7 @@ bool stage_is_gemm(const StageProb& p) { return p.l >= 1 && p.l <= 16; }
 
 int gemm_load_mode(const StageProb& p) {
   const int es = dtype_size(p.vin_dt);
-  const bool fast = p.env_dt == MDBF_F16 && p.l == 16 && (p.K & 7) == 0 && p.K >= 8 &&
+  const bool fast = p.env_dt == MDBF_F16 && (p.l == 16 || p.l == 8) && (p.K & 7) == 0 && p.K >= 8 &&
                     (((uintptr_t)p.vin | (uintptr_t)p.Ein) & 15u) == 0 && ((p.vin_ld * es) & 15) == 0;
   return fast ? p.vin_dt : gemm::kGeneric;
 }

@@ -135,12 +135,16 @@ __global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const Stag
     bool in[4];
     u32x4 raw[4];
     float xk[4];
+    // rank 8: a row of the envelope factor is one 16-byte vector; the lanes of modes 8..15 read it too
+    // and contribute zeros (the matrix-core tile is 16 modes wide whatever the rank)
+    const int hl = p.l >> 3;                    // 16-byte vectors per envelope row: 2 or 1
+    const bool has_modes = (lane & 1) < hl;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int k = k0 + (lane >> 1) + 32 * i;
-      in[i] = k < p.K;
+      in[i] = (k < p.K) && has_modes;
       kc[i] = min(k, p.K - 1);
-      raw[i] = ((g_u32x4_ptr)p.Ein)[(size_t)kc[i] * 2 + (lane & 1)];
+      raw[i] = ((g_u32x4_ptr)p.Ein)[(size_t)kc[i] * hl + (has_modes ? (lane & 1) : 0)];
     }
     const int64_t xrow = (int64_t)b * p.vin_ld;
     if (p.vin_dt == MDBF_F32) {
@@ -264,6 +268,7 @@ struct ItemInfo {
   void* out;
   int64_t out_ld;
   int rows, KB, T, out_dt, flags;
+  int l;                       // envelope rank: 16 or 8
   int tile0, ntl;
   int gt;                      // tiles in the packed layout's group that holds the item
 };
@@ -283,6 +288,7 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.T = w.p.T;
     it.out_dt = w.p.out_dt;
     it.flags = w.p.flags;
+    it.l = w.p.l;
     it.tile0 = w.tile0;
     it.ntl = w.ntiles;
     it.gt = group_tiles(w.tile0, w.p.ntiles);
@@ -297,6 +303,7 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.T = single.T;
     it.out_dt = single.out_dt;
     it.flags = single.flags;
+    it.l = single.l;
     it.tile0 = item * kItemTiles;
     it.ntl = min(kItemTiles, single.ntiles - it.tile0);
     it.gt = group_tiles(it.tile0, single.ntiles);
@@ -337,14 +344,16 @@ __device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, u
   }
 }
 
-// loader: the item's envelope rows (16 modes, fp16: 32 bytes per row) into `stage`
+// loader: the item's envelope rows (l modes of fp16: 32 or 16 bytes per row, rows back to back) into `stage`.
+// With 16-byte rows the second half of the instructions repeats the last row past the item's end.
 __device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane, int lw) {
+  const int hsh = it.l >> 4;                    // log2 of the 16-byte pieces per row: 1 or 0
 #pragma unroll
   for (int j = 0; j < kEoInstr / kLoaderWaves; ++j) {
     const int i = j * kLoaderWaves + lw;
     const int piece = 64 * i + lane;
-    const int row = min(it.tile0 * kTileRows + (piece >> 1), it.rows - 1);
-    dma16(it.Eout, (uint32_t)row * 32u + (uint32_t)(piece & 1) * 16u, stage + i * 1024);
+    const int row = min(it.tile0 * kTileRows + (piece >> hsh), it.rows - 1);
+    dma16(it.Eout, ((uint32_t)row << (4 + hsh)) + (uint32_t)(piece & hsh) * 16u, stage + i * 1024);
   }
 }
 
@@ -504,7 +513,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
             float v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const float ev = (float)eoh[(trel * kTileRows + 4 * kg + i) * 16 + n];
+              const float ev = n < it.l ? (float)eoh[(trel * kTileRows + 4 * kg + i) * it.l + min(n, it.l - 1)] : 0.f;
               const float P = colsum - 2.f * acc[r][i];
               v[i] = row16_sum(ev * P);
             }
@@ -557,7 +566,7 @@ int mx_max_workgroups() { return mx::max_workgroups(); }
 
 bool stage_is_mx(const StageProb& p) {
   // an item's sign words must be addressable with 32-bit offsets from its first tile
-  return p.l == 16 && p.env_dt == MDBF_F16 && p.KB >= 2 && p.xs != nullptr && p.T <= kMaxPreTokens &&
+  return (p.l == 16 || p.l == 8) && p.env_dt == MDBF_F16 && p.KB >= 2 && p.xs != nullptr && p.T <= kMaxPreTokens &&
          (size_t)kGroupTiles * (size_t)p.KB * 256u < (1ull << 31);
 }
 

@@ -101,6 +101,16 @@ def test_pack_argument_errors():
     assert L.mdbf_unpack(FAKE, 4, 0, FAKE, 4, None) == -1
 
 
+def test_pad_envelope_argument_errors():
+    L = mb.lib()
+    assert L.mdbf_pad_envelope(None, 4, 2, 0, FAKE, 8, None) == -1
+    assert L.mdbf_pad_envelope(FAKE, 4, 9, 0, FAKE, 8, None) == -1      # l_to < l
+    assert L.mdbf_pad_envelope(FAKE, 4, 2, 0, FAKE, 17, None) == -1     # beyond the largest rank
+    assert L.mdbf_pad_envelope(FAKE, 0, 2, 0, FAKE, 8, None) == -1
+    assert L.mdbf_pad_envelope(FAKE, 4, 2, 7, FAKE, 8, None) == -3      # unknown element type
+    assert L.mdbf_pad_envelope(FAKE + 2, 4, 2, 0, FAKE, 8, None) == -2
+
+
 def test_batch_plan_errors_and_sizes():
     L = mb.lib()
     arr = (mb.Layer * 2)()

@@ -154,6 +154,17 @@ def test_block_scaled_shapes(gpu, m, n, k, T):
     assert orc.max_rel_error(got, ref) <= TOL
 
 
+@pytest.mark.parametrize("m,n,k,T", [(40, 300, 70, 2), (1100, 1030, 2105, 1), (4096, 4096, 1856, 1), (2064, 520, 4100, 16)])
+def test_block_scaled_rank_8(gpu, m, n, k, T):
+    """Rank-8 envelopes (the 1.0 bits-per-weight budget) through the block-scaled kernel: modes 8..15 of the
+    16-wide matrix-core tile are fed zeros."""
+    L = synth.make_layer(m, n, k, 8, seed=m + 3 * n + 5 * k + 8, env_dtype="f16", env_kind="unit", signed_env=True)
+    X = synth.make_activations(n, T, seed=78 + m, x_dtype="f16")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    got = _run(gpu, L, X, "f16", "f32", block_scaled=True)
+    assert orc.max_rel_error(got, ref) <= TOL
+
+
 @pytest.mark.parametrize("x_dtype,y_dtype", [("bf16", "bf16"), ("f32", "f32"), ("f16", "f16")])
 def test_block_scaled_dtypes(gpu, x_dtype, y_dtype):
     L = synth.make_layer(300, 700, 450, 16, seed=23, env_dtype="f16", env_kind="llama", signed_env=True)
@@ -316,6 +327,8 @@ MANY = [
     (530, 2100, 1100, 16, 100, "f16", "f16"),
     (100, 1030, 200, 1, 130, "f16", "f32"),
     (1100, 520, 2105, 16, 300, "f16", "bf16"),
+    (530, 2100, 1100, 8, 100, "f16", "f16"),
+    (1100, 520, 2104, 8, 40, "f16", "bf16"),
 ]
 
 
@@ -478,3 +491,26 @@ def test_sibling_projections_share_their_input(gpu):
     torch.cuda.synchronize()
     for Yb, ref in zip(Ys, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
+
+
+# ---------------------------------------------------------------- small envelope ranks through zero modes
+@pytest.mark.parametrize("l,l_to,T", [(1, 8, 1), (3, 8, 1), (2, 16, 1), (3, 8, 5)])
+def test_padded_envelopes_denote_the_same_layer(gpu, l, l_to, T):
+    """mdbf_pad_envelope appends zero modes: bit-exact copy plus zeros, and the padded layer (which the
+    matrix-core kernels take) gives the product of the original one."""
+    torch, mb = gpu
+    L = synth.make_layer(530, 2100, 1100, l, seed=400 + l, env_dtype="f16", env_kind="llama", signed_env=True)
+    dl = mb.DeviceLayer.from_host(L)
+    dp = dl.padded(l_to)
+    for name in ("A", "Q", "G", "B"):
+        src, dst = getattr(dl, name).cpu().numpy(), getattr(dp, name).cpu().numpy()
+        assert dst.shape == (src.shape[0], l_to)
+        np.testing.assert_array_equal(dst[:, :l].view(np.uint16), src.view(np.uint16))
+        assert not dst[:, l:].view(np.uint16).any()
+    X = synth.make_activations(2100, T, seed=410, x_dtype="f16")
+    ref = orc.forward_factored(*_oracle_args(L), X)
+    Xd = _to_dev(torch, X, "f16")
+    for layer, bs in ((dl, False), (dp, False), (dp, True)):
+        Y = mb.mdbf_forward(layer, Xd, y_dtype="f32", block_scaled=bs)
+        torch.cuda.synchronize()
+        assert orc.max_rel_error(Y.cpu().numpy().astype(np.float64), ref) <= TOL
