@@ -237,7 +237,9 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
     else if (!forced_mx && T >= kGemmMinTokensSingle && stage_is_gemm(sp[i]))
       e = launch_stage_gemm(nullptr, 0, 0, &sp[i], s);
-    else if (forced_mx || (use_mx(sp[i]) && mx_worthwhile(sp[i].ntiles))) {
+    else if (forced_mx || (use_mx(sp[i]) && (mx_worthwhile(sp[i].ntiles) || !stage_is_fast(sp[i])))) {
+      // (a small launch the fp16 variant cannot take -- rank 8 -- is still better off here than in the
+      // element-wise kernel)
       e = launch_scale_in_mx(nullptr, 1, T * sp[i].KB, &sp[i], s);
       if (e) return hip_fail(e);
       e = launch_stage_mx(nullptr, 0, &sp[i], s);
@@ -280,13 +282,16 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
   h->precise = precise ? 1 : 0;
   // a stage whose problems all qualify for the block-scaled variant is cut into that variant's items
   int mx[2] = {1, 1};
+  int all_fast[2] = {1, 1};
   for (int i = 0; i < count; ++i) {
     const mdbf_layer_t* L = &layers[i];
     StageProb sp[2];
     make_stages(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev, L->ldy, L->T,
                 (void*)(uintptr_t)256, sp);   // placeholder workspace: only the predicates are wanted
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < 2; ++s) {
       if (!use_mx(sp[s])) mx[s] = 0;
+      if (!stage_is_fast(sp[s])) all_fast[s] = 0;
+    }
   }
   int forced = 0, many = 0;
   for (int i = 0; i < count; ++i) {
@@ -296,7 +301,7 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
   }
   h->gemm = (many == count && !precise && forced != count) ? 1 : 0;
   for (int s = 0; s < 2; ++s)
-    if (h->gemm || (forced != count && !mx_worthwhile(tiles[s]))) mx[s] = 0;
+    if (h->gemm || (forced != count && !mx_worthwhile(tiles[s]) && all_fast[s])) mx[s] = 0;
   // otherwise one tile count per work item for both stages keeps one kernel instantiation per plan
   const int tpi_fp16 = mfma_tiles_per_item(tiles[0] < tiles[1] ? tiles[0] : tiles[1]);
   long nitems[2] = {0, 0};
