@@ -10,7 +10,8 @@ the 256 MB last-level cache, so every step streams its weights from HBM.  The ba
 through mdbf_forward_batch (per factor one scale-in launch and one product launch).  Also
 reported, never as `value`: the product kernel timed by itself (the roofline object), the same
 layers issued as one mdbf_forward call each from a HIP graph, one layer re-run hot in cache, the
-latency of a single call, a 16-token call on an MLP projection, and the 2048-token prefill call.
+latency of a single call, a 16-token call on an MLP projection, the 2048-token prefill call, and a plan
+of 96 MLP projections with 1 and with 16 tokens.
 
 Prints ONE JSON line (fields: see the README).
 """
@@ -254,6 +255,36 @@ def main():
 
         extras["decode_T16_mlp_gate"] = time_call(11008, 4096, 4096, 16, 300)
         extras["prefill_T2048_attn"] = time_call(M, N, K, 2048, 300)
+
+        # (6) the MLP projections as they are meant to be issued: 96 independent layers (32 x gate, up, down;
+        #     11008 x 4096 and 4096 x 11008, k = 4096, 0.82 GB) in one plan, with 1 and with 16 tokens each
+        from paper_2512_24545_amd import workloads
+
+        def time_mlp_plan(T, reps):
+            gen = torch.Generator(device="cuda:0")
+            gen.manual_seed(33)
+            pl, px, py, nbytes = [], [], [], 0
+            for _ in range(32):
+                for (m, n) in ((11008, 4096), (11008, 4096), (4096, 11008)):
+                    pl.append(workloads._device_layer(torch, gen, m, n, 4096, L))
+                    px.append(torch.randn((T, n), generator=gen, device="cuda:0").half())
+                    py.append(torch.zeros((T, m), dtype=torch.float16, device="cuda:0"))
+                    nbytes += algorithmic_bytes(m, n, 4096, L, T)
+            plan_mlp = mb.BatchPlan(pl, px, py)
+            for _ in range(reps // 3):
+                plan_mlp.run()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                plan_mlp.run()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            return {"layers": len(pl), "tokens": T, "ms_per_pass": ms, "us_per_layer": ms * 1e3 / len(pl),
+                    "GB/s": nbytes / ms / 1e6, "pct_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS * 100.0}
+
+        extras["mlp_plan_T1"] = time_mlp_plan(1, 300)
+        extras["mlp_plan_T16"] = time_mlp_plan(16, 150)
 
     out = {
         "metric": "MDBF decode GEMV HBM GB/s (% peak) + prefill TFLOP/s, LLaMA-7B shapes",

@@ -289,7 +289,9 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
     make_stages(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev, L->ldy, L->T,
                 (void*)(uintptr_t)256, sp);   // placeholder workspace: only the predicates are wanted
     for (int s = 0; s < 2; ++s) {
-      if (!use_mx(sp[s])) mx[s] = 0;
+      // one envelope rank per launch of the block-scaled kernel
+      if (!use_mx(sp[s]) || (mx[s] != 1 && mx[s] != sp[s].l)) mx[s] = 0;
+      else mx[s] = sp[s].l;
       if (!stage_is_fast(sp[s])) all_fast[s] = 0;
     }
   }
@@ -458,6 +460,7 @@ int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t 
     } else if (h.mx[st]) {
       if (pre_k) e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
       if (e) return hip_fail(e);
+      dummy.l = h.mx[st];
       if (main_k) e = launch_stage_mx(items, h.nitems[st], &dummy, s);
     } else if (h.fast[st]) {
       if (h.pre[st] && pre_k) e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);

@@ -102,7 +102,8 @@ struct PlanHeader {
   int32_t fast[2];            // every problem of the stage qualifies for the fast matrix-core variant
   int32_t pre[2];             // ... and has a buffer for pre-scaled activations (written by the scale-in kernel)
   int32_t max_units[2];       // largest tokens x chunks of a problem of the stage (grid of the scale-in kernel)
-  int32_t mx[2];              // every problem of the stage qualifies for the block-scaled variant
+  int32_t mx[2];              // every problem of the stage qualifies for the block-scaled variant and has this
+                              // envelope rank (16 or 8); 0: the stage runs another variant
   int32_t gemm;               // every layer has kGemmMinTokensPlan tokens or more: many-token variant
   int32_t gemm_mode[2];       // its load mode per stage
   int32_t max_tokens;         // longest token count among the layers
@@ -139,6 +140,7 @@ bool stage_is_mx(const StageProb& p);        // l == 16 or 8, fp16 envelopes, an
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single,
                        hipStream_t s);
 // items_dev null: one problem (`single`), items are cut on the fly
+// single->l = the envelope rank of the launch (16 or 8; a plan's problems all have the same)
 int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s);
 constexpr int kMaxPreTokens = 16;   // token counts up to this use the scale-in kernel
 // true if the fast matrix-core variant can run the problem (l == 16, fp16 envelopes, K % 8 == 0,

@@ -268,7 +268,6 @@ struct ItemInfo {
   void* out;
   int64_t out_ld;
   int rows, KB, T, out_dt, flags;
-  int l;                       // envelope rank: 16 or 8
   int tile0, ntl;
   int gt;                      // tiles in the packed layout's group that holds the item
 };
@@ -288,7 +287,6 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.T = w.p.T;
     it.out_dt = w.p.out_dt;
     it.flags = w.p.flags;
-    it.l = w.p.l;
     it.tile0 = w.tile0;
     it.ntl = w.ntiles;
     it.gt = group_tiles(w.tile0, w.p.ntiles);
@@ -303,7 +301,6 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.T = single.T;
     it.out_dt = single.out_dt;
     it.flags = single.flags;
-    it.l = single.l;
     it.tile0 = item * kItemTiles;
     it.ntl = min(kItemTiles, single.ntiles - it.tile0);
     it.gt = group_tiles(it.tile0, single.ntiles);
@@ -344,10 +341,11 @@ __device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, u
   }
 }
 
-// loader: the item's envelope rows (l modes of fp16: 32 or 16 bytes per row, rows back to back) into `stage`.
-// With 16-byte rows the second half of the instructions repeats the last row past the item's end.
+// loader: the item's envelope rows (RANK modes of fp16: 32 or 16 bytes per row, rows back to back) into
+// `stage`.  With 16-byte rows the second half of the instructions repeats the last row past the item's end.
+template <int RANK>
 __device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane, int lw) {
-  const int hsh = it.l >> 4;                    // log2 of the 16-byte pieces per row: 1 or 0
+  constexpr int hsh = RANK >> 4;                // log2 of the 16-byte pieces per row: 1 or 0
 #pragma unroll
   for (int j = 0; j < kEoInstr / kLoaderWaves; ++j) {
     const int i = j * kLoaderWaves + lw;
@@ -387,7 +385,9 @@ __device__ __forceinline__ void contract_block(const unsigned char* stage, int b
   }
 }
 
-template <bool BATCH>
+// RANK: the envelope rank of every problem of the launch, 16 or 8 (the matrix-core tile is 16 modes wide
+// either way; with 8 the activation records carry zeros in modes 8..15).
+template <bool BATCH, int RANK>
 __global__ __launch_bounds__(kThreads)
 void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -431,7 +431,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
         issue_stage(it, b, t * SB, stage, lane, lw);
         kind_prev = 0;
       } else {
-        issue_eo(it, stage, lane, lw);
+        issue_eo<RANK>(it, stage, lane, lw);
         kind_prev = 1;
       }
       slot = (slot + 1 == kStages) ? 0 : slot + 1;
@@ -513,7 +513,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
             float v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const float ev = n < it.l ? (float)eoh[(trel * kTileRows + 4 * kg + i) * it.l + min(n, it.l - 1)] : 0.f;
+              const float ev = (RANK == 16 || n < RANK) ? (float)eoh[(trel * kTileRows + 4 * kg + i) * RANK + (n & (RANK - 1))] : 0.f;
               const float P = colsum - 2.f * acc[r][i];
               v[i] = row16_sum(ev * P);
             }
@@ -533,20 +533,26 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
 
 static int max_workgroups() { return kWgsPerCu * compute_units(); }
 
-template <bool BATCH>
-static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
+template <bool BATCH, int RANK>
+static int launch_br(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH, RANK>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
   const int max_wgs = max_workgroups();
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
-  hipLaunchKernelGGL((stage_mx_kernel<BATCH>), dim3((unsigned)nwg), dim3(kThreads), kSmemBytes, s, items_dev, nitems,
-                     *single);
+  hipLaunchKernelGGL((stage_mx_kernel<BATCH, RANK>), dim3((unsigned)nwg), dim3(kThreads), kSmemBytes, s, items_dev,
+                     nitems, *single);
   return (int)hipGetLastError();
+}
+
+template <bool BATCH>
+static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
+  if (single->l == 8) return launch_br<BATCH, 8>(items_dev, nitems, single, s);
+  return launch_br<BATCH, 16>(items_dev, nitems, single, s);
 }
 
 }  // namespace mx
