@@ -514,3 +514,17 @@ def test_padded_envelopes_denote_the_same_layer(gpu, l, l_to, T):
         Y = mb.mdbf_forward(layer, Xd, y_dtype="f32", block_scaled=bs)
         torch.cuda.synchronize()
         assert orc.max_rel_error(Y.cpu().numpy().astype(np.float64), ref) <= TOL
+
+
+# ---------------------------------------------------------------- the matrix itself, through unit vectors
+@pytest.mark.parametrize("l,env_dtype", [(16, "f16"), (8, "f16"), (3, "f32")])
+def test_forward_on_the_identity_reproduces_the_dense_matrix(gpu, l, env_dtype):
+    """The product applied to the n unit vectors is What itself (Eq. "me-dbf-basis"), entry by entry."""
+    torch, mb = gpu
+    m, n, k = 200, 192, 96
+    L = synth.make_layer(m, n, k, l, seed=777 + l, env_dtype=env_dtype, env_kind="unit", signed_env=True)
+    W = orc.dense_reconstruct(*_oracle_args(L))
+    got = _run(gpu, L, np.eye(n), "f16", "f32")              # (n, m): row j = What e_j
+    assert np.abs(got.T - W).max() <= TOL * np.abs(W).max()
+    one = _run(gpu, L, np.eye(n)[5:6], "f16", "f32")          # a single unit vector takes the one-token kernels
+    assert np.abs(one[0] - W[:, 5]).max() <= TOL * np.abs(W).max()
