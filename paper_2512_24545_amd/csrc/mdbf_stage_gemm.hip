@@ -340,6 +340,155 @@ void stage_gemm_kernel(const WorkItem* __restrict__ items, StageProb single) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// One short problem by itself (at most 16 tokens, the vector-load modes): the launch above would give each
+// wave one row tile and the whole contraction dimension, a chain of KB dependent steps on a quarter of the
+// device.  Here a workgroup owns ONE row tile and its four waves split the column blocks (wave w takes blocks
+// 4 i + w); an iteration stages four blocks, two iterations ahead; the four partial results meet in LDS and
+// are added in wave order (the same order every time).
+// ---------------------------------------------------------------------------------------------------
+constexpr int kSplitVinBytes = kWaves * 16 * 256;     // four blocks x 16 tokens x 128 columns fp16
+constexpr int kSplitEinBytes = kWaves * kEinBufBytes;
+constexpr int kSplitSmem = 2 * (kSplitVinBytes + kSplitEinBytes);
+
+template <int MODE>
+__global__ __launch_bounds__(64 * kWaves, 2)
+void stage_gemm_split_kernel(StageProb p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* vin_buf = smem;                               // [2][4 blocks][16 tokens][16 chunks], swizzled
+  unsigned char* ein_buf = smem + 2 * kSplitVinBytes;          // [2][4 blocks][128 columns][16 modes]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, g = lane >> 4;
+  const int tile = blockIdx.x;
+  const int KB = p.KB;
+  const int iters = (KB + kWaves - 1) / kWaves;
+
+  // Eout row of this lane's tile row, 4 modes per lane (B operand of the reconstruction)
+  half4 eo_op;
+  {
+    const int row = tile * kTileRows + r16;
+    float v[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int mode = 4 * g + t;
+      v[t] = (row < p.rows && mode < p.l) ? load_as_float(p.Eout, (int64_t)row * p.l + mode, p.env_dt) : 0.f;
+    }
+    eo_op = half4{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+  }
+  const MDBF_GLOBAL uint32_t* sbase = (const MDBF_GLOBAL uint32_t*)p.S + tile_base_words(tile, KB) + lane;
+  const size_t sstride = (size_t)group_tiles(tile, p.ntiles) * 64u;
+
+  // staging of the four blocks of iteration `it`: thread -> (token, chunk) of every block, and (column, half)
+  // of every block's envelope rows.  Columns past K (also whole blocks past KB) get zero envelope rows and
+  // zero activations; tokens past T are never stored.
+  // (values past the end are replaced by zero when a block is parked, not when it is requested: a select
+  // right after the load would make the wave wait for the load there)
+  u32x4 vin_reg[kWaves], ein_reg[kWaves];
+  uint32_t live = 0;                 // bits j: activations of block j hold real data; bits 8 + j: envelope rows
+  uint32_t sw_next;
+  const int st_tok = tid >> 4, st_c = tid & 15;
+  const int hl = p.l >> 3;
+  const bool has_modes = (tid & 1) < hl;
+  auto fetch = [&](int it) {
+    uint32_t lv = 0;
+#pragma unroll
+    for (int j = 0; j < kWaves; ++j) {
+      const int q = it * kWaves + j;
+      const int col = q * kBlockCols + st_c * 8;
+      vin_reg[j] = load8_vec<MODE>(p.vin, (int64_t)min(st_tok, p.T - 1) * p.vin_ld + min(col, p.K - 8));
+      lv |= ((st_tok < p.T) && (col < p.K)) ? (1u << j) : 0u;
+      const int ecol = q * kBlockCols + (tid >> 1);
+      ein_reg[j] = ((const MDBF_GLOBAL u32x4*)p.Ein)[(size_t)min(ecol, p.K - 1) * hl + (has_modes ? (tid & 1) : 0)];
+      lv |= ((ecol < p.K) && has_modes) ? (256u << j) : 0u;
+    }
+    live = lv;
+    sw_next = sbase[(size_t)min(it * kWaves + wave, KB - 1) * sstride];
+  };
+  auto stash = [&](int buf) {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < kWaves; ++j) {
+      *reinterpret_cast<u32x4*>(vin_buf + buf * kSplitVinBytes + j * (16 * 256) + st_tok * 256 +
+                                ((st_c ^ (st_tok & 15)) << 4)) = ((live >> j) & 1u) ? vin_reg[j] : zero;
+      *reinterpret_cast<u32x4*>(ein_buf + buf * kSplitEinBytes + j * kEinBufBytes + ein_row(tid >> 1) * 32 +
+                                (((tid & 1) ^ ((tid >> 5) & 1)) << 4)) = ((live >> (8 + j)) & 1u) ? ein_reg[j] : zero;
+    }
+  };
+
+  fetch(0);
+  stash(0);
+  uint32_t sw = sw_next;
+  fetch(min(1, iters - 1));
+
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int it = 0; it < iters; ++it) {
+    const int cur = it & 1;
+    __syncthreads();
+    const unsigned char* ein = ein_buf + cur * kSplitEinBytes + wave * kEinBufBytes;
+    const unsigned char* vin = vin_buf + cur * kSplitVinBytes + wave * (16 * 256);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+      const int col0 = 32 * f + 8 * (r16 >> 2) + (r16 & 3);
+      const int eoff = ein_row(col0) * 32 + ((g ^ ((r16 >> 2) & 2)) << 3);
+      const half4 ea0 = *reinterpret_cast<const half4*>(ein + eoff);
+      const half4 ea1 = *reinterpret_cast<const half4*>(ein + eoff + (ein_row(4) - ein_row(0)) * 32);
+      const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
+      const floatx4 e0 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea0, eo_op, z4, 0, 0, 0);
+      const floatx4 e1 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea1, eo_op, z4, 0, 0, 0);
+      const int pbase = 8 * (f >> 1) + 4 * (f & 1);
+      uint32_t w4[4];
+      w4[0] = pack_half2(e0[0], e0[1]) ^ ((sw << (15 - (pbase + 0))) & 0x80008000u);
+      w4[1] = pack_half2(e0[2], e0[3]) ^ ((sw << (15 - (pbase + 1))) & 0x80008000u);
+      w4[2] = pack_half2(e1[0], e1[1]) ^ ((sw << (15 - (pbase + 2))) & 0x80008000u);
+      w4[3] = pack_half2(e1[2], e1[3]) ^ ((sw << (15 - (pbase + 3))) & 0x80008000u);
+      const half8 wop = __builtin_bit_cast(half8, u32x4{w4[0], w4[1], w4[2], w4[3]});
+      const int c = f * 4 + g;
+      const half8 a = *reinterpret_cast<const half8*>(vin + r16 * 256 + ((c ^ r16) << 4));
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wop, acc, 0, 0, 0);
+    }
+    stash(cur ^ 1);
+    sw = sw_next;
+    fetch(min(it + 2, iters - 1));
+  }
+
+  // ---- the four partial results: through LDS, added in wave order by wave 0
+  __syncthreads();                                             // every wave is done with the staging buffers
+  floatx4* red = reinterpret_cast<floatx4*>(smem);
+  red[wave * 64 + lane] = acc;
+  __syncthreads();
+  if (wave == 0) {
+    floatx4 sum = red[lane];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+      const floatx4 t = red[w * 64 + lane];
+      sum[0] += t[0]; sum[1] += t[1]; sum[2] += t[2]; sum[3] += t[3];
+    }
+    const int row = tile * kTileRows + r16;
+    if (row < p.rows) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int b = 4 * g + i;
+        if (b < p.T) emit_result(p.out, (int64_t)b * p.out_ld + row, p.out_dt, sum[i], p.flags);
+      }
+    }
+  }
+}
+
+template <int MODE>
+static int launch_split(const StageProb* p, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_split_kernel<MODE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSplitSmem);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((stage_gemm_split_kernel<MODE>), dim3((unsigned)p->ntiles), dim3(64 * kWaves), kSplitSmem, s, *p);
+  return (int)hipGetLastError();
+}
+
 // items_dev null: the single problem *p.  Else nitems work items of a plan, `p` describing the launch:
 // p->T = the longest token count among the problems.
 template <int R, int TB, int MODE, bool BATCH>
@@ -431,6 +580,9 @@ int launch_stage_gemm(const WorkItem* items_dev, int nitems, int mode, const Sta
   }
   if (p->T > 32) return gemm::launch_rt<1, 4>(nullptr, 0, mode, p, s);
   if (p->T > 16) return gemm::launch_rt<1, 2>(nullptr, 0, mode, p, s);
+  if (mode == MDBF_F16) return gemm::launch_split<MDBF_F16>(p, s);
+  if (mode == MDBF_BF16) return gemm::launch_split<MDBF_BF16>(p, s);
+  if (mode == MDBF_F32) return gemm::launch_split<MDBF_F32>(p, s);
   return gemm::launch_rt<1, 1>(nullptr, 0, mode, p, s);
 }
 
