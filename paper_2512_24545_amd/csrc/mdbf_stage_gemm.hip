@@ -351,7 +351,7 @@ constexpr int kSplitVinBytes = kWaves * 16 * 256;     // four blocks x 16 tokens
 constexpr int kSplitEinBytes = kWaves * kEinBufBytes;
 constexpr int kSplitSmem = 2 * (kSplitVinBytes + kSplitEinBytes);
 
-template <int MODE>
+template <int MODE, int R>
 __global__ __launch_bounds__(64 * kWaves, 2)
 void stage_gemm_split_kernel(StageProb p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -360,24 +360,28 @@ void stage_gemm_split_kernel(StageProb p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r16 = lane & 15, g = lane >> 4;
-  const int tile = blockIdx.x;
+  const int tile0 = blockIdx.x * R;                            // this workgroup's R consecutive row tiles
   const int KB = p.KB;
   const int iters = (KB + kWaves - 1) / kWaves;
 
   // Eout row of this lane's tile row, 4 modes per lane (B operand of the reconstruction)
-  half4 eo_op;
-  {
-    const int row = tile * kTileRows + r16;
+  half4 eo_op[R];
+  const MDBF_GLOBAL uint32_t* sbase[R];
+  size_t sstride[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int row = (tile0 + r) * kTileRows + r16;
     float v[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int mode = 4 * g + t;
       v[t] = (row < p.rows && mode < p.l) ? load_as_float(p.Eout, (int64_t)row * p.l + mode, p.env_dt) : 0.f;
     }
-    eo_op = half4{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+    eo_op[r] = half4{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+    const int t = min(tile0 + r, p.ntiles - 1);               // a tile past the end repeats the last (never stored)
+    sbase[r] = (const MDBF_GLOBAL uint32_t*)p.S + tile_base_words(t, KB) + lane;
+    sstride[r] = (size_t)group_tiles(t, p.ntiles) * 64u;
   }
-  const MDBF_GLOBAL uint32_t* sbase = (const MDBF_GLOBAL uint32_t*)p.S + tile_base_words(tile, KB) + lane;
-  const size_t sstride = (size_t)group_tiles(tile, p.ntiles) * 64u;
 
   // staging of the four blocks of iteration `it`: thread -> (token, chunk) of every block, and (column, half)
   // of every block's envelope rows.  Columns past K (also whole blocks past KB) get zero envelope rows and
@@ -386,7 +390,7 @@ void stage_gemm_split_kernel(StageProb p) {
   // right after the load would make the wave wait for the load there)
   u32x4 vin_reg[kWaves], ein_reg[kWaves];
   uint32_t live = 0;                 // bits j: activations of block j hold real data; bits 8 + j: envelope rows
-  uint32_t sw_next;
+  uint32_t sw_next[R];
   const int st_tok = tid >> 4, st_c = tid & 15;
   const int hl = p.l >> 3;
   const bool has_modes = (tid & 1) < hl;
@@ -403,7 +407,8 @@ void stage_gemm_split_kernel(StageProb p) {
       lv |= ((ecol < p.K) && has_modes) ? (256u << j) : 0u;
     }
     live = lv;
-    sw_next = sbase[(size_t)min(it * kWaves + wave, KB - 1) * sstride];
+#pragma unroll
+    for (int r = 0; r < R; ++r) sw_next[r] = sbase[r][(size_t)min(it * kWaves + wave, KB - 1) * sstride[r]];
   };
   auto stash = [&](int buf) {
     const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -418,10 +423,15 @@ void stage_gemm_split_kernel(StageProb p) {
 
   fetch(0);
   stash(0);
-  uint32_t sw = sw_next;
+  uint32_t sw[R];
+  floatx4 acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    sw[r] = sw_next[r];
+    acc[r] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
   fetch(min(1, iters - 1));
 
-  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
   for (int it = 0; it < iters; ++it) {
     const int cur = it & 1;
@@ -434,39 +444,44 @@ void stage_gemm_split_kernel(StageProb p) {
       const int eoff = ein_row(col0) * 32 + ((g ^ ((r16 >> 2) & 2)) << 3);
       const half4 ea0 = *reinterpret_cast<const half4*>(ein + eoff);
       const half4 ea1 = *reinterpret_cast<const half4*>(ein + eoff + (ein_row(4) - ein_row(0)) * 32);
-      const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
-      const floatx4 e0 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea0, eo_op, z4, 0, 0, 0);
-      const floatx4 e1 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea1, eo_op, z4, 0, 0, 0);
-      const int pbase = 8 * (f >> 1) + 4 * (f & 1);
-      uint32_t w4[4];
-      w4[0] = pack_half2(e0[0], e0[1]) ^ ((sw << (15 - (pbase + 0))) & 0x80008000u);
-      w4[1] = pack_half2(e0[2], e0[3]) ^ ((sw << (15 - (pbase + 1))) & 0x80008000u);
-      w4[2] = pack_half2(e1[0], e1[1]) ^ ((sw << (15 - (pbase + 2))) & 0x80008000u);
-      w4[3] = pack_half2(e1[2], e1[3]) ^ ((sw << (15 - (pbase + 3))) & 0x80008000u);
-      const half8 wop = __builtin_bit_cast(half8, u32x4{w4[0], w4[1], w4[2], w4[3]});
       const int c = f * 4 + g;
       const half8 a = *reinterpret_cast<const half8*>(vin + r16 * 256 + ((c ^ r16) << 4));
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wop, acc, 0, 0, 0);
+      const int pbase = 8 * (f >> 1) + 4 * (f & 1);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
+        const floatx4 e0 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea0, eo_op[r], z4, 0, 0, 0);
+        const floatx4 e1 = __builtin_amdgcn_mfma_f32_16x16x16f16(ea1, eo_op[r], z4, 0, 0, 0);
+        uint32_t w4[4];
+        w4[0] = pack_half2(e0[0], e0[1]) ^ ((sw[r] << (15 - (pbase + 0))) & 0x80008000u);
+        w4[1] = pack_half2(e0[2], e0[3]) ^ ((sw[r] << (15 - (pbase + 1))) & 0x80008000u);
+        w4[2] = pack_half2(e1[0], e1[1]) ^ ((sw[r] << (15 - (pbase + 2))) & 0x80008000u);
+        w4[3] = pack_half2(e1[2], e1[3]) ^ ((sw[r] << (15 - (pbase + 3))) & 0x80008000u);
+        const half8 wop = __builtin_bit_cast(half8, u32x4{w4[0], w4[1], w4[2], w4[3]});
+        acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wop, acc[r], 0, 0, 0);
+      }
     }
     stash(cur ^ 1);
-    sw = sw_next;
+#pragma unroll
+    for (int r = 0; r < R; ++r) sw[r] = sw_next[r];
     fetch(min(it + 2, iters - 1));
   }
 
   // ---- the four partial results: through LDS, added in wave order by wave 0
   __syncthreads();                                             // every wave is done with the staging buffers
-  floatx4* red = reinterpret_cast<floatx4*>(smem);
-  red[wave * 64 + lane] = acc;
+  floatx4* red = reinterpret_cast<floatx4*>(smem);              // [R][4 waves][64 lanes]
+#pragma unroll
+  for (int r = 0; r < R; ++r) red[(r * kWaves + wave) * 64 + lane] = acc[r];
   __syncthreads();
-  if (wave == 0) {
-    floatx4 sum = red[lane];
+  if (wave < R) {                                              // wave r adds up and stores tile r
+    floatx4 sum = red[(wave * kWaves) * 64 + lane];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) {
-      const floatx4 t = red[w * 64 + lane];
+      const floatx4 t = red[(wave * kWaves + w) * 64 + lane];
       sum[0] += t[0]; sum[1] += t[1]; sum[2] += t[2]; sum[3] += t[3];
     }
-    const int row = tile * kTileRows + r16;
-    if (row < p.rows) {
+    const int row = (tile0 + wave) * kTileRows + r16;
+    if (tile0 + wave < p.ntiles && row < p.rows) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int b = 4 * g + i;
@@ -476,17 +491,28 @@ void stage_gemm_split_kernel(StageProb p) {
   }
 }
 
-template <int MODE>
-static int launch_split(const StageProb* p, hipStream_t s) {
+// R row tiles per workgroup (wave r stores tile r): more tiles mean fewer re-reads of the envelope rows and
+// activations (every workgroup reads all of them) but longer chains and fewer workgroups.
+template <int MODE, int R>
+static int launch_split_r(const StageProb* p, hipStream_t s) {
+  static_assert(R >= 1 && R <= kWaves, "wave r stores tile r");
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_split_kernel<MODE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_split_kernel<MODE, R>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSplitSmem);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((stage_gemm_split_kernel<MODE>), dim3((unsigned)p->ntiles), dim3(64 * kWaves), kSplitSmem, s, *p);
+  hipLaunchKernelGGL((stage_gemm_split_kernel<MODE, R>), dim3((unsigned)((p->ntiles + R - 1) / R)),
+                     dim3(64 * kWaves), kSplitSmem, s, *p);
   return (int)hipGetLastError();
+}
+
+// one tile per workgroup as long as the device holds all workgroups at once (two per compute unit)
+template <int MODE>
+static int launch_split(const StageProb* p, hipStream_t s) {
+  if (p->ntiles > 2 * compute_units()) return launch_split_r<MODE, 2>(p, s);
+  return launch_split_r<MODE, 1>(p, s);
 }
 
 // items_dev null: the single problem *p.  Else nitems work items of a plan, `p` describing the launch:
