@@ -548,3 +548,43 @@ def test_short_single_calls(gpu, m, n, k, l, T, x_dtype):
     assert orc.max_rel_error(got, ref) <= TOL
     again = _run(gpu, L, X, x_dtype, "f32")
     np.testing.assert_array_equal(got, again)     # the partial sums are added in a fixed order
+
+
+# ---------------------------------------------------------------- HIP graph capture and replay
+@pytest.mark.parametrize("T,block_scaled", [(1, False), (1, True), (6, False)])
+def test_graph_replay_matches_eager(gpu, T, block_scaled):
+    """A plan captured into a HIP graph: every replay, with new activations in the same buffers and eager
+    work in between, gives exactly what the eager call gives (the library records kernel launches only)."""
+    torch, mb = gpu
+    specs = [(530, 2104, 1104, 16), (272, 1032, 4096, 16), (1024, 1024, 640, 8)]
+    layers, Xs, Ys = [], [], []
+    for i, (m, n, k, l) in enumerate(specs):
+        L = synth.make_layer(m, n, k, l, seed=600 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+        layers.append(mb.DeviceLayer.from_host(L))
+        Xs.append(torch.zeros((T, n), dtype=torch.float16, device="cuda:0"))
+        Ys.append(torch.zeros((T, m), dtype=torch.float32, device="cuda:0"))
+    plan = mb.BatchPlan(layers, Xs, Ys, block_scaled=block_scaled)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        plan.run(stream=s)                       # warm-up outside the capture (function attributes)
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        plan.run(stream=s)
+    for rep in range(3):
+        new = [synth.make_activations(X.shape[1], T, seed=700 + 10 * rep + i, x_dtype="f16") for i, X in enumerate(Xs)]
+        for X, a in zip(Xs, new):
+            X.copy_(_to_dev(torch, a, "f16"))
+        for Y in Ys:
+            Y.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        replayed = [Y.clone() for Y in Ys]
+        for Y in Ys:
+            Y.zero_()
+        plan.run()
+        torch.cuda.synchronize()
+        for Yr, Ye in zip(replayed, Ys):
+            assert torch.equal(Yr, Ye)
+            assert Ye.abs().max().item() > 0
