@@ -588,3 +588,19 @@ def test_graph_replay_matches_eager(gpu, T, block_scaled):
         for Yr, Ye in zip(replayed, Ys):
             assert torch.equal(Yr, Ye)
             assert Ye.abs().max().item() > 0
+
+
+# ---------------------------------------------------------------- a residual stack as one launch
+@pytest.mark.parametrize("ranks,T", [((4, 4), 1), ((8, 8), 1), ((1, 1), 1), ((8, 8), 6)])
+def test_residual_stack_as_one_concatenated_layer(gpu, ranks, T):
+    """P independently factorised terms with sum of ranks <= 16, written as one layer (sign bases
+    concatenated along the inner dimension, block-diagonal inner envelope factors): one call instead of P
+    accumulating ones; ranks adding up to 8 or 16 take the matrix-core kernels."""
+    terms = [synth.make_layer(530, 1032, 520 + 8 * p, l, seed=820 + p, env_dtype="f16", env_kind="llama", signed_env=True)
+             for p, l in enumerate(ranks)]
+    X = synth.make_activations(1032, T, seed=830, x_dtype="f16")
+    ref = orc.forward_residual_stack([_oracle_args(t) for t in terms], X)
+    one = synth.concat_terms(terms)
+    assert orc.max_rel_error(_run(gpu, one, X, "f16", "f32"), ref) <= TOL
+    if sum(ranks) in (8, 16) and T == 1:
+        assert orc.max_rel_error(_run(gpu, one, X, "f16", "f32", block_scaled=True), ref) <= TOL

@@ -256,3 +256,17 @@ def test_residual_stack_is_the_sum_of_dense_terms():
     np.testing.assert_allclose(orc.forward_residual_stack(terms, X), X @ Wsum.T, rtol=1e-12, atol=1e-12)
     # a planted mistake (a term dropped) is seen
     assert not np.allclose(orc.forward_residual_stack(terms[:2], X), X @ Wsum.T)
+
+
+def test_residual_stack_is_one_layer_of_concatenated_factors():
+    # sum_p U_p V_p = [U_1 .. U_P] [V_1; ..; V_P]: sign bases concatenated along the inner dimension, outer
+    # envelope factors side by side, inner ones block-diagonal (rank sum l_p)
+    terms = [synth.make_layer(9, 11, k, l, seed=70 + k, env_dtype="f32", env_kind="unit", signed_env=True)
+             for k, l in ((5, 2), (7, 1), (4, 3))]
+    X = synth.make_activations(11, 3, seed=71, x_dtype="f32")
+    one = synth.concat_terms(terms)
+    assert one["k"] == 16 and one["l"] == 6
+    np.testing.assert_allclose(orc.forward_factored(*_args(one), X),
+                               orc.forward_residual_stack([_args(t) for t in terms], X), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(orc.dense_reconstruct(*_args(one)),
+                               sum(orc.dense_reconstruct(*_args(t)) for t in terms), rtol=1e-12, atol=1e-12)
