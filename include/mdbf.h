@@ -136,13 +136,11 @@ int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out);
  * S_A o (A Q^T), S_B o (G B^T) are rebuilt piece by piece in fp16 and applied as dense products to the
  * fp16-rounded activations (x and z; z is stored in fp16 between the two products).  Magnitudes above
  * 65504 in those fp16 quantities overflow.
- * Range of the fp16 quantities: the one-token fp16 variant (single calls, small plans) stages b^(s) o x and
- * q^(t) o z divided by up to 8 and keeps full accuracy while those products stay above about 5e-4 in
- * magnitude (below, fp16 runs out of normal numbers; below 5e-7 it flushes to zero); the many-token variant
- * needs the entries of A Q^T and G B^T and the activations inside fp16's normal range (6e-5 .. 65504).  The
- * block-scaled variant has neither limit (per-32-value exponents of fp32 range; MDBF_FLAG_BLOCK_SCALED selects
- * it wherever it applies).  What is unchanged when A is divided and B multiplied by the same positive constant
- * (likewise Q, G): a layer whose intermediate products fall outside these ranges can be rebalanced offline.
+ * Range: the one-token variants carry their own power-of-two exponents (the block-scaled one per 32 values,
+ * the fp16 one per 1024 columns of a scaled-activation vector) and keep z in fp32: they hold their accuracy
+ * wherever the inputs and results are representable.  The many-token variant needs the entries of A Q^T and
+ * G B^T, the activations and z inside fp16's normal range (6e-5 .. 65504); What is unchanged when A is divided
+ * and B multiplied by the same positive constant (likewise Q, G), so a layer can be rebalanced offline.
  * With MDBF_FLAG_PRECISE everything is fp32 vector arithmetic. */
 int mdbf_forward(const mdbf_desc_t* desc,
                  const void* SA_packed_dev, const void* SB_packed_dev,

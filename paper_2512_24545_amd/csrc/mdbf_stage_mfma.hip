@@ -146,8 +146,9 @@ __device__ __forceinline__ void stage_load(const void* ein, int ch, const void* 
 
 // dst: the thread's 8 consecutive 16-byte slots (modes 8ch..8ch+7 of its octet); slot cc is stored at
 // cc ^ sw so that the 64 lanes of one store instruction spread over all LDS banks.
-__device__ __forceinline__ void stage_store(const StageRegs& sr, int vin_dt, u32x4* dst, int sw) {
-  // activations as fp32, times 2^-(e/2) (the position factor of the sign expansion), times the K mask
+__device__ __forceinline__ void stage_store(const StageRegs& sr, int vin_dt, u32x4* dst, int sw, float scale) {
+  // activations as fp32, times 2^-(e/2) (the position factor of the sign expansion), times the K mask,
+  // times the chunk's power-of-two scale (1 when the kernel stages for itself)
   float x[8];
   const u32x4 x0 = sr.xr[0], x1 = sr.xr[1];
   if (vin_dt == MDBF_F32) {
@@ -169,7 +170,7 @@ __device__ __forceinline__ void stage_store(const StageRegs& sr, int vin_dt, u32
     }
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) x[e] *= sr.vmask * (1.0f / (float)(1 << (e >> 1)));
+  for (int e = 0; e < 8; ++e) x[e] *= (sr.vmask * scale) * (1.0f / (float)(1 << (e >> 1)));
 #pragma unroll
   for (int cc = 0; cc < 8; ++cc) {
     u32x4 v;
@@ -183,6 +184,39 @@ __device__ __forceinline__ void stage_store(const StageRegs& sr, int vin_dt, u32
     }
     dst[cc ^ sw] = v;
   }
+}
+
+// 2^d for an integer -126 <= d <= 127
+__device__ __forceinline__ float pow2i(int d) { return __builtin_bit_cast(float, (uint32_t)(127 + d) << 23); }
+
+// Largest |Ein[k, c] * vin[k]| over the thread's octet of columns and its eight modes (0 outside K).
+__device__ __forceinline__ float stage_absmax(const StageRegs& sr, int vin_dt) {
+  float x[8];
+  const u32x4 x0 = sr.xr[0], x1 = sr.xr[1];
+  if (vin_dt == MDBF_F32) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(float, (e < 4) ? x0[e & 3] : x1[e & 3]);
+  } else if (vin_dt == MDBF_F16) {
+    const half8 xh = __builtin_bit_cast(half8, x0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = (float)xh[e];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t wd = x0[e >> 1];
+      x[e] = __builtin_bit_cast(float, (e & 1) ? (wd & 0xFFFF0000u) : (wd << 16));
+    }
+  }
+  float m = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const half8 row = __builtin_bit_cast(half8, sr.e[e]);
+    float rm = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) rm = fmaxf(rm, fabsf((float)row[j]));
+    m = fmaxf(m, rm * fabsf(x[e]));
+  }
+  return m * sr.vmask;
 }
 
 // How a workgroup gets the scaled activations of a chunk into LDS.
@@ -204,7 +238,7 @@ struct Stager<false> {
   }
   __device__ __forceinline__ void load_part(int part) { stage_load_part(sa, part, sr); }
   __device__ __forceinline__ void store(u32x4* bufbase, int st_vec, int st_sw, int /*tid*/) {
-    stage_store(sr, vin_dt, bufbase + st_vec, st_sw);
+    stage_store(sr, vin_dt, bufbase + st_vec, st_sw, 1.0f);
   }
 };
 
@@ -278,6 +312,7 @@ struct Unit {
   const uint32_t* sbase[R];
   const void* vin_row;
   const u32x4* xs_tok;   // pre-scaled activations of the unit's token (all chunks), or null
+  const int* xs_exp;     // their power-of-two exponents, one per chunk (behind the activations of all tokens)
 };
 
 template <int R>
@@ -293,6 +328,7 @@ __device__ __forceinline__ void finish_unit(Unit<R>& u, int wave) {
   u.vin_row = (const char*)u.p.vin + (size_t)u.b * (size_t)u.p.vin_ld * (size_t)dtype_size(u.p.vin_dt);
   const int nch = (u.p.KB + CB - 1) / CB;
   u.xs_tok = (const u32x4*)u.p.xs + (size_t)u.b * (size_t)nch * (size_t)kChunkVecs;
+  u.xs_exp = (const int*)((const u32x4*)u.p.xs + (size_t)u.p.T * (size_t)nch * (size_t)kChunkVecs) + (size_t)u.b * nch;
 }
 
 // In batch mode the 128-byte work item is fetched one dword per lane and broadcast to scalar registers
@@ -405,6 +441,10 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
   stg.store(buf, st_vec, st_sw, tid);
   __syncthreads();
 
+  // Pre-scaled activations come with one power-of-two exponent per chunk (the scale-in kernel puts every
+  // chunk's largest magnitude at 2^12): the accumulators are carried in the current chunk's scale and
+  // brought to the next chunk's at the boundary; the result is scaled back at the end.
+  int e_cur = PRE ? ((const MDBF_GLOBAL int*)u.xs_exp)[0] : 0;
   DBG_UNIT_DECL;
   for (;;) {
     DBG_UNIT_NEXT;
@@ -429,6 +469,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
 
     const int KB = u.p.KB;
     const int nchunks = (KB + CB - 1) / CB;
+    int e_unit_next = 0;
 
     // ---- all chunks but the last.  The sign words and the envelope rows of the next chunk are requested
     //      up front, into registers of their own, and have the whole chunk to arrive; blocks that do
@@ -436,6 +477,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
     uint32_t wnext[R][kPrefetchBlocks];
 #pragma unroll 1
     for (int c = 0; c < nchunks - 1; ++c) {
+      const int e_nx = PRE ? ((const MDBF_GLOBAL int*)u.xs_exp)[c + 1] : 0;
       stg.addr(u.p.Ein, u.vin_row, u.p.vin_dt, u.xs_tok, c + 1, u.p.K, ch, st_col, tid);
       DBG_T(1 + 4 * c);
       const u32x4* bufc = buf + par * kChunkVecs;
@@ -473,6 +515,19 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
       for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int j = 0; j < kPrefetchBlocks; ++j) wq[r][j] = wnext[r][j];
+      if (PRE) {
+        const float f = pow2i(max(-126, min(127, e_nx - e_cur)));
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[r][0][i] *= f;
+            acc[r][1][i] *= f;
+          }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) accv[i] *= f;
+        e_cur = e_nx;
+      }
     }
 
     // ---- the last chunk.  All loads of the next unit (its first chunk of sign words and of envelope
@@ -489,6 +544,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
         make_unit<R, BATCH>(desc_next, single, tiles_per_item, ni, wave, un);
       }
       stg.addr(un.p.Ein, un.vin_row, un.p.vin_dt, un.xs_tok, 0, un.p.K, ch, st_col, tid);
+      e_unit_next = PRE ? ((const MDBF_GLOBAL int*)un.xs_exp)[0] : 0;
       u32x4 eoreg[eo_vecs(R) / 256];
 #pragma unroll
       for (int t = 0; t < eo_vecs(R) / 256; ++t) {
@@ -534,6 +590,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
     DBG_T(40);
     const float colsum = (red[n] + red[16 + n]) + (red[32 + n] + red[48 + n]);
     const _Float16* eoh = reinterpret_cast<const _Float16*>(eo);
+    const float unscale = PRE ? pow2i(-e_cur) : 1.f;
     float res[R];   // lane (kg, n < 4) ends up with the result of row 4*kg + n of tile r
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -546,7 +603,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
         v[i] = row16_sum(ev * P);
       }
       const int sel = n & 3;
-      res[r] = sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3];
+      res[r] = (sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3]) * unscale;
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -554,6 +611,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
       if ((wave + 4 * r) < u.ntl && n < 4 && row < u.p.rows)
         emit_result(u.p.out, (int64_t)u.b * u.p.out_ld + row, u.p.out_dt, res[r], u.p.flags);
     }
+    e_cur = e_unit_next;
     DBG_T(41);
     if (!has_next) break;
     // a one-chunk unit writes red / eo again before any other barrier: wait for the slowest reader
@@ -616,8 +674,24 @@ __global__ __launch_bounds__(256) void scale_in_kernel(const StageProb* __restri
   const void* vin_row = (const char*)p.vin + (size_t)b * (size_t)p.vin_ld * (size_t)dtype_size(p.vin_dt);
   StageRegs sr;
   stage_load(p.Ein, ch, vin_row, p.vin_dt, c * (CB * kBlockCols) + st_col, p.K, sr);
+  // the chunk's largest magnitude goes to [2^12, 2^13): the smallest position factor (1/8) still leaves
+  // three decades of normal fp16 numbers below it, the largest stays a factor 8 under fp16's overflow
+  __shared__ float wmax[4];
+  float m = stage_absmax(sr, p.vin_dt);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if ((tid & 63) == 0) wmax[tid >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+  int e = 0;
+  if (m > 0.f && m < 3.0e38f) {
+    int ex;
+    (void)frexpf(m, &ex);                     // m = fr * 2^ex, fr in [0.5, 1)
+    e = min(max(13 - ex, -100), 100);
+  }
   u32x4* dst = (u32x4*)p.xs + ((size_t)b * nch + c) * (size_t)kChunkVecs + st_vec;
-  stage_store(sr, p.vin_dt, dst, st_sw);
+  stage_store(sr, p.vin_dt, dst, st_sw, pow2i(e));
+  if (tid == 0) ((MDBF_GLOBAL int*)((u32x4*)p.xs + (size_t)p.T * nch * (size_t)kChunkVecs))[(size_t)b * nch + c] = e;
 }
 
 int launch_scale_in(const StageProb* probs_dev, int count, int max_units, const StageProb* single, hipStream_t s) {
@@ -627,7 +701,8 @@ int launch_scale_in(const StageProb* probs_dev, int count, int max_units, const 
 
 size_t xs_bytes_for(int K, int T) {
   const int nch = (num_blocks(K) + CB - 1) / CB;
-  return (size_t)T * (size_t)nch * (size_t)kChunkVecs * 16u;
+  // the staged chunks of every token, then one exponent per (token, chunk)
+  return (size_t)T * (size_t)nch * (size_t)kChunkVecs * 16u + (((size_t)T * (size_t)nch * 4u + 15u) & ~(size_t)15u);
 }
 
 #ifdef MDBF_DBG_TIMING

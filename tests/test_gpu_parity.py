@@ -607,7 +607,8 @@ def test_residual_stack_as_one_concatenated_layer(gpu, ranks, T):
 
 
 # ---------------------------------------------------------------- magnitudes far from one
-@pytest.mark.parametrize("env_scale,x_scale", [(0.5, 1.0), (32.0, 2.0 ** -10), (1.0, 512.0), (4.0, 2.0 ** -4)])
+@pytest.mark.parametrize("env_scale,x_scale", [(0.5, 1.0), (32.0, 2.0 ** -10), (1.0, 512.0), (4.0, 2.0 ** -4), (0.25, 1.0),
+                                               (0.5, 2.0 ** -6)])
 @pytest.mark.parametrize("variant", ["auto", "block_scaled", "tokens"])
 def test_relative_error_does_not_depend_on_scale(gpu, env_scale, x_scale, variant):
     """Envelopes and activations scaled by powers of two, the scaled activations B o x and Q o z (divided by
@@ -625,15 +626,16 @@ def test_relative_error_does_not_depend_on_scale(gpu, env_scale, x_scale, varian
 
 
 @pytest.mark.parametrize("env_scale,x_scale", [(2.0 ** -9, 1.0), (2.0 ** -6, 2.0 ** -12), (2.0 ** -3, 2.0 ** -14)])
-def test_block_scaled_records_carry_their_own_exponents(gpu, env_scale, x_scale):
-    """Far below fp16's normal range (the scaled activations Q o z reach 1e-12 here, which fp16 staging
-    flushes to zero) the block-scaled variant still meets the gate: its records hold fp32-range exponents
-    per 32 values, and z stays in fp32."""
+@pytest.mark.parametrize("block_scaled", [True, False])
+def test_one_token_variants_carry_their_own_exponents(gpu, env_scale, x_scale, block_scaled):
+    """Far below fp16's normal range (the scaled activations Q o z reach 1e-12 here) both one-token variants
+    still meet the gate: the block-scaled records hold an exponent per 32 values, the fp16 variant's
+    scale-in kernel one per 1024 columns, and z stays in fp32."""
     L = synth.make_layer(530, 2104, 1104, 16, seed=941, env_dtype="f16", env_kind="llama", signed_env=True)
     for key in ("A", "Q", "G", "B"):
         L[key] = synth.round_to_dtype(L[key].astype(np.float64) * env_scale, "f16")
     X = synth.round_to_dtype(synth.make_activations(2104, 1, seed=942, x_dtype="f32").astype(np.float64) * x_scale, "f16")
     ref = orc.forward_factored(*_oracle_args(L), X)
     assert np.abs(ref).max() > 0
-    got = _run(gpu, L, X, "f16", "f32", block_scaled=True)
+    got = _run(gpu, L, X, "f16", "f32", block_scaled=block_scaled)
     assert orc.max_rel_error(got, ref) <= TOL
