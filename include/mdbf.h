@@ -138,7 +138,9 @@ int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out);
  * 65504 in those fp16 quantities overflow.
  * Range: the one-token variants carry their own power-of-two exponents (the block-scaled one per 32 values,
  * the fp16 one per 1024 columns of a scaled-activation vector) and keep z in fp32: they hold their accuracy
- * wherever the inputs and results are representable.  The many-token variant needs the entries of A Q^T and
+ * wherever the inputs and results are representable.  The general kernel (other ranks and envelope types) stages
+ * b^(s) o x and q^(t) o z in plain fp16, divided by up to 8: magnitudes below about 5e-4 lose accuracy.  The
+ * many-token variant needs the entries of A Q^T and
  * G B^T, the activations and z inside fp16's normal range (6e-5 .. 65504); What is unchanged when A is divided
  * and B multiplied by the same positive constant (likewise Q, G), so a layer can be rebalanced offline.
  * With MDBF_FLAG_PRECISE everything is fp32 vector arithmetic. */
