@@ -210,10 +210,14 @@ __device__ __forceinline__ float stage_absmax(const StageRegs& sr, int vin_dt) {
   float m = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const half8 row = __builtin_bit_cast(half8, sr.e[e]);
-    float rm = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) rm = fmaxf(rm, fabsf((float)row[j]));
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+    const u32x4 w = sr.e[e];
+    const half2v a0 = __builtin_elementwise_abs(__builtin_bit_cast(half2v, w.x));
+    const half2v a1 = __builtin_elementwise_abs(__builtin_bit_cast(half2v, w.y));
+    const half2v a2 = __builtin_elementwise_abs(__builtin_bit_cast(half2v, w.z));
+    const half2v a3 = __builtin_elementwise_abs(__builtin_bit_cast(half2v, w.w));
+    const half2v mm = __builtin_elementwise_max(__builtin_elementwise_max(a0, a1), __builtin_elementwise_max(a2, a3));
+    const float rm = fmaxf((float)mm.x, (float)mm.y);
     m = fmaxf(m, rm * fabsf(x[e]));
   }
   return m * sr.vmask;
