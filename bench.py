@@ -185,6 +185,21 @@ def main():
             "scale_in_avg_launch_us": avg_scale_in_ms * 1e3,
             "scale_in_algorithmic_bytes_per_launch": scale_in_bytes_layer * a.copies}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # the read bandwidth a plain kernel reaches on this device (16-byte loads over 1 GiB, 8 workgroups of 256
+    # lanes per compute unit): the practical ceiling next to the nominal peak
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    sink = torch.zeros(8192, dtype=torch.int32, device="cuda:0")
+    for _ in range(5):
+        mb.mdbf_stream_read(buf, sink)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(50):
+        mb.mdbf_stream_read(buf, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    roof["stream_read_GBps"] = 50 * buf.numel() / e0.elapsed_time(e1) / 1e6
+    roof["frac_of_stream_read"] = roof["achieved"] / roof["stream_read_GBps"]
+    del buf, sink
 
     extras = {}
     if not a.no_extras:

@@ -186,6 +186,16 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
 int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t plan_bytes, int stages,
                             int kernels, void* stream);
 
+/* Measurement aid: reads `bytes` bytes at src_dev once with plain 16-byte loads and folds them with XOR;
+ * wave w of the launch stores the fold of the 32-bit words it read in sink_dev[w].  The launch has
+ * sink_words waves (sink_words / 4 workgroups of 256 lanes; element i of the buffer, in 16-byte units, is
+ * read by lane i mod (64 * sink_words)), so the XOR of sink_dev[0 .. sink_words) is the XOR of all 32-bit
+ * words of the buffer.  Timed over a buffer far larger than the caches it gives the read bandwidth a kernel
+ * can reach on this device, the yardstick next to the nominal HBM peak for the decode kernels (whose
+ * work is streaming the packed signs of paper Sec. 3.2 once).
+ * bytes: positive multiple of 16; sink_words: multiple of 4 in [4, 1 << 20]; pointers 16-byte aligned. */
+int mdbf_stream_read(const void* src_dev, size_t bytes, uint32_t* sink_dev, int sink_words, void* stream);
+
 /* ---- misc ----------------------------------------------------------------------------- */
 const char* mdbf_strerror(int status);
 const char* mdbf_last_hip_error(void);   /* text of the last failed HIP call on this thread, or "" */

@@ -24,7 +24,7 @@ STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE",
 
 EXPORTS = [
     "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack", "mdbf_pad_envelope",
-    "mdbf_workspace_bytes", "mdbf_forward", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
+    "mdbf_stream_read", "mdbf_workspace_bytes", "mdbf_forward", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
     "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
 ]
 
@@ -74,6 +74,7 @@ def lib():
     L.mdbf_pack.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
     L.mdbf_unpack.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
     L.mdbf_pad_envelope.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+    L.mdbf_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
     L.mdbf_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int, C.POINTER(C.c_size_t)]
     L.mdbf_forward.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.POINTER(Env), C.c_void_p, C.c_int64,
                                C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -165,6 +166,15 @@ def mdbf_pad_envelope(env, l_to, stream=None):
     _check(lib().mdbf_pad_envelope(env.data_ptr(), env.shape[0], env.shape[1], DTYPE_CODE[_dtype_name(env)],
                                    out.data_ptr(), l_to, _stream_ptr(stream)), "mdbf_pad_envelope")
     return out
+
+
+def mdbf_stream_read(src, sink, stream=None):
+    """src: contiguous CUDA tensor whose size in bytes is a multiple of 16; sink: int32 CUDA tensor with a
+    multiple of 4 elements, one per wave of the launch.  XOR of sink = XOR of the 32-bit words of src."""
+    assert src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.is_contiguous()
+    _check(lib().mdbf_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), sink.numel(),
+                                  _stream_ptr(stream)), "mdbf_stream_read")
+    return sink
 
 
 class DeviceLayer:

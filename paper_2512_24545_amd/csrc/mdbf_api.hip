@@ -205,6 +205,13 @@ int mdbf_pad_envelope(const void* env_dev, int rows, int l, int dtype, void* out
   return hip_fail(launch_pad_envelope(env_dev, rows, l, out_dev, l_to, dtype_size(dtype), (hipStream_t)stream));
 }
 
+int mdbf_stream_read(const void* src_dev, size_t bytes, uint32_t* sink_dev, int sink_words, void* stream) {
+  if (!src_dev || !sink_dev || bytes == 0 || (bytes & 15) != 0) return MDBF_EINVAL;
+  if (sink_words < 4 || sink_words > (1 << 20) || (sink_words & 3) != 0) return MDBF_EINVAL;
+  if (!aligned16(src_dev) || !aligned16(sink_dev)) return MDBF_EALIGN;
+  return hip_fail(launch_stream_read(src_dev, bytes, sink_dev, sink_words, (hipStream_t)stream));
+}
+
 int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out) {
   int st = check_desc(desc);
   if (st) return st;

@@ -118,6 +118,7 @@ constexpr uint32_t kPlanMagic = 0x4D444246u;  // "MDBF"
 int launch_pack(const int8_t* signs, int rows, int cols, int64_t ld, uint32_t* packed, hipStream_t s);
 int launch_unpack(const uint32_t* packed, int rows, int cols, int8_t* signs, int64_t ld, hipStream_t s);
 int launch_pad_envelope(const void* src, int rows, int l, void* dst, int l_to, int es, hipStream_t s);
+int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int sink_words, hipStream_t s);
 int launch_stage_precise(const StageProb* probs_dev, const WorkItem* items_dev, int nitems,
                          const StageProb* single, hipStream_t s);
 // pre: the problems' xs buffers hold the pre-scaled activations (launch_scale_in ran before)

@@ -83,4 +83,33 @@ int launch_pad_envelope(const void* src, int rows, int l, void* dst, int l_to, i
   return (int)hipGetLastError();
 }
 
+// Plain streaming read: lane t of the launch reads the 16-byte elements t, t + lanes, t + 2 * lanes, ...
+// (four independent loads per trip) and XORs them; every wave stores one word.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink) {
+  const MDBF_GLOBAL u32x4_t* g = (const MDBF_GLOBAL u32x4_t*)src;
+  const size_t lanes = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  u32x4_t a0 = {0, 0, 0, 0}, a1 = a0, a2 = a0, a3 = a0;
+  for (; i + 3 * lanes < n16; i += 4 * lanes) {
+    a0 ^= __builtin_nontemporal_load(g + i);
+    a1 ^= __builtin_nontemporal_load(g + i + lanes);
+    a2 ^= __builtin_nontemporal_load(g + i + 2 * lanes);
+    a3 ^= __builtin_nontemporal_load(g + i + 3 * lanes);
+  }
+  for (; i < n16; i += lanes) a0 ^= __builtin_nontemporal_load(g + i);
+  a0 ^= a1 ^ a2 ^ a3;
+  uint32_t v = a0.x ^ a0.y ^ a0.z ^ a0.w;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v ^= (uint32_t)__shfl_xor((int)v, d);
+  if ((threadIdx.x & 63) == 0) ((MDBF_GLOBAL uint32_t*)sink)[blockIdx.x * 4 + (threadIdx.x >> 6)] = v;
+}
+
+int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int sink_words, hipStream_t s) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)(sink_words / 4)), dim3(256), 0, s, (const u32x4_t*)src,
+                     bytes / 16, sink);
+  return (int)hipGetLastError();
+}
+
 }  // namespace mdbf

@@ -6,17 +6,21 @@
 // v_mfma_scale_f32_16x16x128_f8f6f4: one instruction contracts a whole 128-column block of a 16-row tile.
 //
 //  * A operand (signs) in fp4 (e2m1).  A lane's 32 sign bits of a block are one 32-bit word w; the four
-//    operand registers are  w & 0x11111111, w & 0x22222222, w & 0x44444444, (w >> 1) & 0x44444444 :
-//    every nibble is 0 or the single-bit pattern of 0.5, 1, 2, 2.  Five vector operations expand 32 signs
-//    (the fp16 variant needs 17).  With bit t = 1 meaning -1, S = 1 - 2t, so P = colsum - 2 * sum t*xs.
+//    operand registers are  w & 0x11111111, w & 0x22222222, w & 0x44444444, (w & 0x88888888) | 0x22222222 :
+//    in the first three every nibble is 0 or the single-bit pattern of 0.5, 1, 2; in the fourth the bit is the
+//    fp4 sign of a 1.0, i.e. the sign S itself.  Four vector operations expand 32 signs (the fp16 variant
+//    needs 17).  With bit t = 1 meaning -1, S = 1 - 2t: over the first three registers' columns
+//    P = colsum - 2 * sum t*xs; the fourth register's columns carry -xs/2, so that the same -2 * acc adds
+//    their sum S*xs.
 //  * B operand (activations) in three fp6 (e2m3) limbs with one power-of-two scale per lane and block
 //    (32 values): xs' = L1*2^E + L2*2^(E-4) + L3*2^(E-8) to about 2^-13 of the block maximum, where
-//    xs' = xs / {0.5,1,2,2} undoes the value of the sign nibble.  Three MFMAs per tile and block, all into
+//    xs' = xs / {0.5,1,2,-2} undoes the value of the sign nibble.  Three MFMAs per tile and block, all into
 //    one fp32 accumulator; the hardware applies the scales.
 //  * The limbs are produced once per (problem, token) by mx_scale_in_kernel as a stream of 5120-byte block
 //    records; the main kernel does no arithmetic on activations.
-//  * colsum[c] = sum_j xs[j,c] is taken over the quantised values by the scale-in kernel (exact in fp32 per
-//    element, one partial sum per block and mode) and travels inside each block record.
+//  * colsum[c] = sum_j xs[j,c] over the columns of the first three operand registers is taken over the
+//    quantised values by the scale-in kernel (exact in fp32 per element, one partial sum per block and
+//    mode) and travels inside each block record.
 //
 // The main kernel is split by role.  A workgroup has eight contraction waves (eight row tiles each) and two
 // loader waves.  The loaders move sign words, activation records and envelope rows from global memory
@@ -102,7 +106,8 @@ __host__ __device__ constexpr int local_col_of_element(int j, int kg) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// scale-in kernel: one wave per (problem, token, 128-column block).
+// scale-in kernel: one record per (problem, token, 128-column block); a wave builds `per_wave` consecutive
+// records of a problem, fetching the inputs of the next one before it works on the current one.
 //   1. the block's products Ein[k,c] * vin[k] (fp32; zero for k >= K) go to LDS, 128 x 16
 //   2. lane (kg, n) gathers its 32 values in operand order, undoes the nibble values, takes the block
 //      exponent E (largest magnitude <= 7.5 * 2^E) and peels three fp6 limbs at scales E, E-4, E-8;
@@ -111,79 +116,74 @@ __host__ __device__ constexpr int local_col_of_element(int j, int kg) {
 // ---------------------------------------------------------------------------------------------------
 constexpr int kProdStride = 18;   // floats per LDS row: lane groups 8 rows apart land on disjoint banks
 constexpr int kPrepWaves = 4;
+constexpr int kPrepMaxPerWave = 4;
 
-__global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const StageProb* __restrict__ probs,
-                                                                      StageProb single) {
-  __shared__ __attribute__((aligned(16))) float prod[kPrepWaves][128 * kProdStride];
-  StageProb p;
-  if (probs) p = probs[blockIdx.y];
-  else p = single;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int unit = blockIdx.x * kPrepWaves + wv;        // (token, block)
-  const bool live = unit < p.KB * p.T;
-  const int b = live ? unit / p.KB : 0, q = live ? unit - b * p.KB : 0;
+// inputs of one record as they come from memory: lane handles rows lane/2 + 32 i, modes 8 (lane & 1) .. + 7
+struct PrepInput {
+  u32x4 raw[4];      // eight envelope entries (fp16) per row
+  uint32_t xbits[4]; // the row's activation: fp32 bits, or fp16 / bf16 bits in the low half
+};
+
+__device__ __forceinline__ PrepInput prep_load(const StageProb& p, int unit, int lane) {
+  const int b = unit / p.KB, q = unit - b * p.KB;
+  // rank 8: a row of the envelope factor is one 16-byte vector; the lanes of modes 8..15 read it too
+  // and contribute zeros (the matrix-core tile is 16 modes wide whatever the rank)
+  const int hl = p.l >> 3;                    // 16-byte vectors per envelope row: 2 or 1
+  const bool has_modes = (lane & 1) < hl;
+  const int64_t xrow = (int64_t)b * p.vin_ld;
+  PrepInput in;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int kc = min(q * kBlockCols + (lane >> 1) + 32 * i, p.K - 1);
+    in.raw[i] = ((g_u32x4_ptr)p.Ein)[(size_t)kc * hl + (has_modes ? (lane & 1) : 0)];
+    in.xbits[i] = (p.vin_dt == MDBF_F32) ? ((g_u32_ptr)p.vin)[xrow + kc] : (uint32_t)((g_u16_ptr)p.vin)[xrow + kc];
+  }
+  return in;
+}
+
+// all lanes of the wave have finished their LDS accesses issued so far (a wave's LDS operations execute in
+// order: this only keeps the compiler from moving accesses across)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ void prep_record(const StageProb& p, int unit, int lane, const PrepInput& in, float* pr) {
+  const int b = unit / p.KB, q = unit - b * p.KB;
   const int kg = lane >> 4, n = lane & 15;
   unsigned char* blk = (unsigned char*)p.xs + ((size_t)b * p.KB + q) * (size_t)kBlockBytes;
-  const int k0 = q * kBlockCols;
-  float* pr = prod[wv];
+  const bool has_modes = (lane & 1) < (p.l >> 3);
 
-  // ---- 1. products: lane handles rows lane/2 + 32 i, modes 8 (lane & 1) .. + 7.  All eight loads are
-  //         issued before the first use (one memory round trip per wave).
-  {
-    int kc[4];
-    bool in[4];
-    u32x4 raw[4];
-    float xk[4];
-    // rank 8: a row of the envelope factor is one 16-byte vector; the lanes of modes 8..15 read it too
-    // and contribute zeros (the matrix-core tile is 16 modes wide whatever the rank)
-    const int hl = p.l >> 3;                    // 16-byte vectors per envelope row: 2 or 1
-    const bool has_modes = (lane & 1) < hl;
+  // ---- 1. products
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int k = k0 + (lane >> 1) + 32 * i;
-      in[i] = (k < p.K) && has_modes;
-      kc[i] = min(k, p.K - 1);
-      raw[i] = ((g_u32x4_ptr)p.Ein)[(size_t)kc[i] * hl + (has_modes ? (lane & 1) : 0)];
-    }
-    const int64_t xrow = (int64_t)b * p.vin_ld;
-    if (p.vin_dt == MDBF_F32) {
+  for (int i = 0; i < 4; ++i) {
+    const bool live = (q * kBlockCols + (lane >> 1) + 32 * i < p.K) && has_modes;
+    const float xk = (p.vin_dt == MDBF_F32)   ? __builtin_bit_cast(float, in.xbits[i])
+                     : (p.vin_dt == MDBF_F16) ? (float)__builtin_bit_cast(_Float16, (uint16_t)in.xbits[i])
+                                              : __builtin_bit_cast(float, in.xbits[i] << 16);
+    const uint32_t w[4] = {in.raw[i].x, in.raw[i].y, in.raw[i].z, in.raw[i].w};
+    float* dst = pr + ((lane >> 1) + 32 * i) * kProdStride + (lane & 1) * 8;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) xk[i] = ((g_f32_ptr)p.vin)[xrow + kc[i]];
-    } else {
-      uint16_t h[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) h[i] = ((g_u16_ptr)p.vin)[xrow + kc[i]];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        xk[i] = (p.vin_dt == MDBF_F16) ? (float)__builtin_bit_cast(_Float16, h[i])
-                                       : __builtin_bit_cast(float, (uint32_t)h[i] << 16);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
-      float* dst = pr + ((lane >> 1) + 32 * i) * kProdStride + (lane & 1) * 8;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] & 0xFFFFu));
-        const float hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] >> 16));
-        dst[2 * t] = in[i] ? lo * xk[i] : 0.f;
-        dst[2 * t + 1] = in[i] ? hi * xk[i] : 0.f;
-      }
+    for (int t = 0; t < 4; ++t) {
+      const float lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] & 0xFFFFu));
+      const float hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] >> 16));
+      dst[2 * t] = live ? lo * xk : 0.f;
+      dst[2 * t + 1] = live ? hi * xk : 0.f;
     }
   }
-  __syncthreads();
-  if (!live) return;
+  wave_lds_sync();
 
   // ---- 2. gather in operand order, quantise
   float val[32];
   float m = 0.f;
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
-    const float presc = (j < 8) ? 2.f : (j < 16 ? 1.f : 0.5f);   // undo the nibble values 0.5, 1, 2, 2
+    const float presc = (j < 8) ? 2.f : (j < 16 ? 1.f : (j < 24 ? 0.5f : -0.5f));   // undo the nibble values 0.5, 1, 2, -2
     val[j] = pr[(local_col_of_element(j, 0) + 8 * kg) * kProdStride + n] * presc;
     m = fmaxf(m, fabsf(val[j]));
   }
+  wave_lds_sync();   // the next record's products may overwrite the buffer
   int E = -100;
   if (m > 0.f) {
     int ex;
@@ -206,12 +206,12 @@ __global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const Stag
   for (int j = 0; j < 32; ++j) r[j] -= b2[j];
   const v6u l3 = fp6_encode32(r, sc3);
   const v32f b3 = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(l3, sc3);
-  // quantised value = val - (last residual); back at the scale of xs, summed over the lane's 32 columns
+  // quantised value = val - (last residual); back at the scale of xs, summed over the lane's columns
   float part = 0.f;
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
     const float inv = (j < 8) ? 0.5f : (j < 16 ? 1.f : 2.f);
-    part += (val[j] - (r[j] - b3[j])) * inv;
+    if (j < 24) part += (val[j] - (r[j] - b3[j])) * inv;   // the fourth register's columns need no fix-up
   }
   const v6u limb[3] = {l1, l2, l3};
 #pragma unroll
@@ -232,15 +232,50 @@ __global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const Stag
   if (lane < 16) ((MDBF_GLOBAL float*)(blk + kColsumOff))[lane] = part;
 }
 
+__global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const StageProb* __restrict__ probs,
+                                                                      StageProb single, int per_wave) {
+  __shared__ __attribute__((aligned(16))) float prod[kPrepWaves][128 * kProdStride];
+  StageProb p;
+  if (probs) p = probs[blockIdx.y];
+  else p = single;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int units = p.KB * p.T;                          // (token, block) pairs of the problem
+  int unit = (blockIdx.x * kPrepWaves + wv) * per_wave;
+  const int end = min(unit + per_wave, units);
+  if (unit >= end) return;
+  float* pr = prod[wv];
+  PrepInput cur = prep_load(p, unit, lane);
+  for (; unit < end; ++unit) {
+    PrepInput next = cur;
+    if (unit + 1 < end) next = prep_load(p, unit + 1, lane);
+    prep_record(p, unit, lane, cur, pr);
+    cur = next;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------------
 // main kernel
 // ---------------------------------------------------------------------------------------------------
-__device__ __forceinline__ v8i sign_operand(uint32_t w) {
+// The constants of the fourth operand register, held in registers the optimiser cannot see through: the
+// three-operand and-or instruction takes no literal constants on this target.
+struct SignConsts {
+  uint32_t sign_bits;   // 0x88888888, scalar register
+  uint32_t ones;        // 0x22222222 (1.0 in every nibble), vector register
+};
+__device__ __forceinline__ SignConsts sign_consts() {
+  SignConsts c;
+  asm("s_mov_b32 %0, 0x88888888" : "=s"(c.sign_bits));
+  asm("v_mov_b32 %0, 0x22222222" : "=v"(c.ones));
+  return c;
+}
+
+__device__ __forceinline__ v8i sign_operand(uint32_t w, const SignConsts& k) {
   v8i r;
   r[0] = (int)(w & 0x11111111u);
   r[1] = (int)(w & 0x22222222u);
   r[2] = (int)(w & 0x44444444u);
-  r[3] = (int)((w >> 1) & 0x44444444u);
+  r[3] = (int)((w & k.sign_bits) | k.ones);
   r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0;
   return r;
 }
@@ -308,80 +343,181 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
   return it;
 }
 
-// one loader instruction: 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS at `lds`
+// one loader instruction: 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS at `lds`.
+// STREAM: data read once per launch (sign words, envelope rows) carries the non-temporal hint: measured on
+// this chip, streaming reads reach about 7.2 TB/s with it and 6.0 - 6.3 TB/s without.
+template <bool STREAM>
 __device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t lane_off, unsigned char* lds) {
-  __builtin_amdgcn_global_load_lds((const MDBF_GLOBAL void*)(gbase + lane_off), (MDBF_LDS void*)lds, 16, 0, 0);
+  constexpr int kNonTemporal = 2;   // cache-policy operand of the instruction: bit 1 = nt
+  __builtin_amdgcn_global_load_lds((const MDBF_GLOBAL void*)(gbase + lane_off), (MDBF_LDS void*)lds, 16, 0,
+                                   STREAM ? kNonTemporal : 0);
 }
 
-// loader wave lw (it takes every kLoaderWaves-th instruction): blocks [q0, q0 + SB) of the item's tiles and
-// of token b's activation stream into `stage`
+// Lane offsets of the sign-word instructions of loader wave LW (it takes every kLoaderWaves-th instruction):
+// instruction 2 * jj + LW of a block carries tiles 4 * (2 * jj + LW) .. + 3, 16 bytes per lane; tiles past
+// the item's end repeat its last tile.  One set per item, so that an instruction costs no vector arithmetic.
+constexpr int kSignInstrPerBlock = kItemTiles / 4 / kLoaderWaves;
+template <int LW>
+__device__ __forceinline__ void sign_lane_offsets(const ItemInfo& it, int lane, uint32_t (&voff)[kSignInstrPerBlock]) {
+#pragma unroll
+  for (int jj = 0; jj < kSignInstrPerBlock; ++jj) {
+    const int trel = min((jj * kLoaderWaves + LW) * 4 + (lane >> 4), it.ntl - 1);
+    voff[jj] = (uint32_t)trel * 256u + (uint32_t)(lane & 15) * 16u;
+  }
+}
+
+// loader wave LW: blocks [q0, q0 + SB) of the item's tiles and of token b's activation stream into `stage`
+template <int LW>
 __device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, unsigned char* stage, int lane,
-                                            int lw) {
+                                            const uint32_t (&voff)[kSignInstrPerBlock]) {
   // activation records: each record is five instructions; a block past the end repeats the last one
 #pragma unroll
   for (int j = 0; j < kXsInstr / kLoaderWaves; ++j) {
-    const int i = j * kLoaderWaves + lw;
-    const int blk = i / (kBlockBytes / 1024), part = i - blk * (kBlockBytes / 1024);
+    constexpr int kPerRecord = kBlockBytes / 1024;
+    const int i = j * kLoaderWaves + LW;
+    const int blk = i / kPerRecord, part = i - blk * kPerRecord;
     const int q = min(q0 + blk, it.KB - 1);
     const unsigned char* src = it.xs + ((size_t)b * it.KB + q) * (size_t)kBlockBytes;
-    dma16(src + part * 1024, (uint32_t)lane * 16u, stage + i * 1024);
+    dma16<false>(src + part * 1024, (uint32_t)lane * 16u, stage + i * 1024);
   }
   // sign words: in the packed layout the item's tiles of one block are contiguous (256 bytes per tile);
-  // instruction i carries four tiles of one block, 16 bytes per lane.  Tiles past the item's end repeat
-  // its last tile, a block past the end repeats the last block.
+  // a block past the end repeats the last block
   const unsigned char* ibase = it.S + tile_base_words(it.tile0, it.KB) * 4u;
   const uint32_t bstride = (uint32_t)it.gt * 256u;
 #pragma unroll
   for (int j = 0; j < kSignInstr / kLoaderWaves; ++j) {
-    const int i = j * kLoaderWaves + lw;
+    const int i = j * kLoaderWaves + LW;
     const int blk = i / (kItemTiles / 4);
-    const int trel = min((i - blk * (kItemTiles / 4)) * 4 + (lane >> 4), it.ntl - 1);
-    const uint32_t off = (uint32_t)min(q0 + blk, it.KB - 1) * bstride + (uint32_t)trel * 256u + (uint32_t)(lane & 15) * 16u;
-    dma16(ibase, off, stage + kStageXs + i * 1024);
+    const unsigned char* bbase = ibase + (size_t)((uint32_t)min(q0 + blk, it.KB - 1) * bstride);
+    dma16<true>(bbase, voff[j % kSignInstrPerBlock], stage + kStageXs + i * 1024);
   }
 }
 
 // loader: the item's envelope rows (RANK modes of fp16: 32 or 16 bytes per row, rows back to back) into
 // `stage`.  With 16-byte rows the second half of the instructions repeats the last row past the item's end.
-template <int RANK>
-__device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane, int lw) {
+template <int RANK, int LW>
+__device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane) {
   constexpr int hsh = RANK >> 4;                // log2 of the 16-byte pieces per row: 1 or 0
 #pragma unroll
   for (int j = 0; j < kEoInstr / kLoaderWaves; ++j) {
-    const int i = j * kLoaderWaves + lw;
+    const int i = j * kLoaderWaves + LW;
     const int piece = 64 * i + lane;
     const int row = min(it.tile0 * kTileRows + (piece >> hsh), it.rows - 1);
-    dma16(it.Eout, ((uint32_t)row << (4 + hsh)) + (uint32_t)(piece & hsh) * 16u, stage + i * 1024);
+    dma16<true>(it.Eout, ((uint32_t)row << (4 + hsh)) + (uint32_t)(piece & hsh) * 16u, stage + i * 1024);
   }
 }
 
-// one 128-column block of a stage: R tiles of this wave against the block's three limbs.  Tiles past the
-// item's end are contracted too (their sign words repeat the last tile's; the results are not stored):
-// skipping them costs more registers and branches than it saves.
-__device__ __forceinline__ void contract_block(const unsigned char* stage, int blk, int lane, int n, int wave,
-                                               floatx4 (&acc)[R], float& colsum) {
+// What a contraction wave reads from LDS for one 128-column block of a stage: the block's three limbs with
+// their scales and column sum, and the sign words of the wave's R tiles.
+struct BlockOperands {
+  v8i limb[3];
+  uint32_t scales;
+  float colsum;
+  uint32_t w[R];
+};
+
+__device__ __forceinline__ BlockOperands read_block(const unsigned char* stage, int blk, int lane, int n, int wave) {
   const unsigned char* rec = stage + blk * kBlockBytes;
-  v8i bl[3];
+  BlockOperands o;
 #pragma unroll
   for (int L = 0; L < 3; ++L) {
     const u32x4 a = reinterpret_cast<const u32x4*>(rec + L * kLimbBytes)[lane];
     const u32x2 c = reinterpret_cast<const u32x2*>(rec + L * kLimbBytes + 64 * 16)[lane];
-    bl[L][0] = (int)a.x; bl[L][1] = (int)a.y; bl[L][2] = (int)a.z; bl[L][3] = (int)a.w;
-    bl[L][4] = (int)c.x; bl[L][5] = (int)c.y; bl[L][6] = 0; bl[L][7] = 0;
+    o.limb[L][0] = (int)a.x; o.limb[L][1] = (int)a.y; o.limb[L][2] = (int)a.z; o.limb[L][3] = (int)a.w;
+    o.limb[L][4] = (int)c.x; o.limb[L][5] = (int)c.y; o.limb[L][6] = 0; o.limb[L][7] = 0;
   }
-  const uint32_t sc = reinterpret_cast<const uint32_t*>(rec + kScaleOff)[lane];
-  colsum += reinterpret_cast<const float*>(rec + kColsumOff)[n];
+  o.scales = reinterpret_cast<const uint32_t*>(rec + kScaleOff)[lane];
+  o.colsum = reinterpret_cast<const float*>(rec + kColsumOff)[n];
   const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage + kStageXs) + blk * kItemTiles * 64 + lane;
+#pragma unroll
+  for (int r = 0; r < R; ++r) o.w[r] = sw[(wave + kComputeWaves * r) * 64];
+  return o;
+}
+
+// R tiles of this wave against the block's three limbs.  Tiles past the item's end are contracted too
+// (their sign words repeat the last tile's; the results are not stored): skipping them costs more
+// registers and branches than it saves.
+__device__ __forceinline__ void contract_block(const BlockOperands& o, floatx4 (&acc)[R], float& colsum,
+                                               const SignConsts& k) {
+  colsum += o.colsum;
   v8i a[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) a[r] = sign_operand(sw[(wave + kComputeWaves * r) * 64]);
+  for (int r = 0; r < R; ++r) a[r] = sign_operand(o.w[r], k);
   // limb outermost: consecutive instructions write different accumulators
 #pragma unroll
   for (int L = 0; L < 3; ++L) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      acc[r] = mx_mfma(a[r], bl[L], acc[r], L, sc);
+      acc[r] = mx_mfma(a[r], o.limb[L], acc[r], L, o.scales);
     }
+  }
+}
+
+// The loader role of wave LW of a workgroup: walks the workgroup's stage sequence (for every item, for
+// every token, ceil(KB / SB) contraction stages followed by one stage with the envelope rows; stage g lives
+// in ring slot g % kStages), two stages ahead of the contraction waves.  Barrier g opens stage g for them
+// and tells the loader that stage g - 1 has been drained, so that its slot can take stage g + 2.
+template <bool BATCH, int RANK, int LW>
+__device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, const StageProb& single, int item0,
+                                            int i_hi, int stride, unsigned char* smem, int lane) {
+  int item = item0;
+  ItemInfo it = load_item<BATCH>(items, single, item);
+  uint32_t voff[kSignInstrPerBlock];
+  sign_lane_offsets<LW>(it, lane, voff);
+  int b = 0, t = 0;                       // cursor: next stage to issue = stage t of (item, b)
+  int nst = (it.KB + SB - 1) / SB;        // contraction stages of the cursor's unit
+  bool more = true;                       // the cursor points at an existing stage
+  int slot = 0;                           // ring slot of the next stage to issue
+  int kind_prev = 0;                      // kind of the newest issued stage: 0 contraction, 1 envelope rows
+  auto issue_next = [&]() {
+    unsigned char* stage = smem + slot * kStageBytes;
+    if (t < nst) {
+      issue_stage<LW>(it, b, t * SB, stage, lane, voff);
+      kind_prev = 0;
+    } else {
+      issue_eo<RANK, LW>(it, stage, lane);
+      kind_prev = 1;
+    }
+    slot = (slot + 1 == kStages) ? 0 : slot + 1;
+    // advance the cursor
+    if (t < nst) {
+      ++t;
+    } else {
+      t = 0;
+      if (b + 1 < it.T) {
+        ++b;
+      } else {
+        b = 0;
+        item += stride;
+        if (item < i_hi) {
+          it = load_item<BATCH>(items, single, item);
+          sign_lane_offsets<LW>(it, lane, voff);
+          nst = (it.KB + SB - 1) / SB;
+        } else {
+          more = false;
+        }
+      }
+    }
+  };
+  // prologue: stages 0 and 1 (every unit has at least two stages)
+  issue_next();
+  issue_next();
+  int outstanding = 2;                    // issued stages not yet handed over
+  for (;;) {
+    // hand over the oldest outstanding stage: all but the newest stage's loads must have landed
+    if (outstanding == 2) {
+      if (kind_prev == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kXsInstr + kSignInstr) / kLoaderWaves) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kEoInstr / kLoaderWaves) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    asm volatile("s_barrier" ::: "memory");
+    --outstanding;
+    if (more) {
+      issue_next();
+      ++outstanding;
+    }
+    if (outstanding == 0) break;
   }
 }
 
@@ -410,74 +546,16 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   }
   if (item0 >= i_hi) return;
 
-  // Stage sequence of this workgroup, the same for both roles: for every item, for every token,
-  // ceil(KB / SB) contraction stages followed by one stage with the envelope rows.  Stage g lives in
-  // ring slot g % kStages.  Barrier g opens stage g for the contraction waves and tells the loader that
-  // stage g - 1 has been drained, so that its slot can take stage g + 2.
-
+  // both roles walk the same stage sequence (see loader_role); one barrier per stage
   if (wave >= kComputeWaves) {
-    const int lw = wave - kComputeWaves;
-    // =========================== loader ===========================
-    int item = item0;
-    ItemInfo it = load_item<BATCH>(items, single, item);
-    int b = 0, t = 0;                       // cursor: next stage to issue = stage t of (item, b)
-    int nst = (it.KB + SB - 1) / SB;        // contraction stages of the cursor's unit
-    bool more = true;                       // the cursor points at an existing stage
-    int slot = 0;                           // ring slot of the next stage to issue
-    int kind_prev = 0;                      // kind of the newest issued stage: 0 contraction, 1 envelope rows
-    auto issue_next = [&]() {
-      unsigned char* stage = smem + slot * kStageBytes;
-      if (t < nst) {
-        issue_stage(it, b, t * SB, stage, lane, lw);
-        kind_prev = 0;
-      } else {
-        issue_eo<RANK>(it, stage, lane, lw);
-        kind_prev = 1;
-      }
-      slot = (slot + 1 == kStages) ? 0 : slot + 1;
-      // advance the cursor
-      if (t < nst) {
-        ++t;
-      } else {
-        t = 0;
-        if (b + 1 < it.T) {
-          ++b;
-        } else {
-          b = 0;
-          item += stride;
-          if (item < i_hi) {
-            it = load_item<BATCH>(items, single, item);
-            nst = (it.KB + SB - 1) / SB;
-          } else {
-            more = false;
-          }
-        }
-      }
-    };
-    // prologue: stages 0 and 1 (every unit has at least two stages)
-    issue_next();
-    issue_next();
-    int outstanding = 2;                    // issued stages not yet handed over
-    for (;;) {
-      // hand over the oldest outstanding stage: all but the newest stage's loads must have landed
-      if (outstanding == 2) {
-        if (kind_prev == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kXsInstr + kSignInstr) / kLoaderWaves) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kEoInstr / kLoaderWaves) : "memory");
-      } else {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      }
-      asm volatile("s_barrier" ::: "memory");
-      --outstanding;
-      if (more) {
-        issue_next();
-        ++outstanding;
-      }
-      if (outstanding == 0) break;
-    }
+    static_assert(kLoaderWaves == 2, "one instantiation of the loader role per loader wave");
+    if (wave == kComputeWaves) loader_role<BATCH, RANK, 0>(items, single, item0, i_hi, stride, smem, lane);
+    else loader_role<BATCH, RANK, 1>(items, single, item0, i_hi, stride, smem, lane);
     return;
   }
 
   // =========================== contraction waves ===========================
+  const SignConsts sconst = sign_consts();
   int item = item0;
   ItemInfo it = load_item<BATCH>(items, single, item);
   int slot = 0;
@@ -497,7 +575,8 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
 #pragma unroll
         for (int blk = 0; blk < SB; ++blk) {
           if (t * SB + blk < it.KB) {
-            contract_block(stage, blk, lane, n, wave, acc, colsum);
+            const BlockOperands o = read_block(stage, blk, lane, n, wave);
+            contract_block(o, acc, colsum, sconst);
           }
         }
       }
@@ -558,9 +637,15 @@ static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* sing
 }  // namespace mx
 
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single, hipStream_t s) {
-  const int wgs = (max_units + mx::kPrepWaves - 1) / mx::kPrepWaves;
+  // records per wave: as many as it takes for the launch to be resident at once (four workgroups per
+  // compute unit: their LDS), so that a wave's memory round trips overlap its own arithmetic
+  const long resident = (long)compute_units() * 4 * mx::kPrepWaves;
+  long per_wave = ((long)count * max_units + resident - 1) / resident;
+  per_wave = per_wave < 1 ? 1 : per_wave > mx::kPrepMaxPerWave ? mx::kPrepMaxPerWave : per_wave;
+  const int waves = (max_units + (int)per_wave - 1) / (int)per_wave;
+  const int wgs = (waves + mx::kPrepWaves - 1) / mx::kPrepWaves;
   hipLaunchKernelGGL(mx::mx_scale_in_kernel, dim3((unsigned)wgs, (unsigned)count), dim3(64 * mx::kPrepWaves), 0, s,
-                     probs_dev, *single);
+                     probs_dev, *single, (int)per_wave);
   return (int)hipGetLastError();
 }
 

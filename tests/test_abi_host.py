@@ -111,6 +111,18 @@ def test_pad_envelope_argument_errors():
     assert L.mdbf_pad_envelope(FAKE + 2, 4, 2, 0, FAKE, 8, None) == -2
 
 
+def test_stream_read_argument_errors():
+    L = mb.lib()
+    assert L.mdbf_stream_read(None, 1024, FAKE, 8, None) == -1
+    assert L.mdbf_stream_read(FAKE, 1024, None, 8, None) == -1
+    assert L.mdbf_stream_read(FAKE, 0, FAKE, 8, None) == -1
+    assert L.mdbf_stream_read(FAKE, 1000, FAKE, 8, None) == -1          # not a multiple of 16 bytes
+    assert L.mdbf_stream_read(FAKE, 1024, FAKE, 6, None) == -1          # whole workgroups only
+    assert L.mdbf_stream_read(FAKE, 1024, FAKE, 0, None) == -1
+    assert L.mdbf_stream_read(FAKE, 1024, FAKE, (1 << 20) + 4, None) == -1
+    assert L.mdbf_stream_read(FAKE + 4, 1024, FAKE, 8, None) == -2
+
+
 def test_batch_plan_errors_and_sizes():
     L = mb.lib()
     arr = (mb.Layer * 2)()

@@ -85,6 +85,21 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("nbytes,waves", [(16, 4), (16 * 1000, 4), (16 * 65537, 64), (1 << 22, 8192), ((1 << 22) + 48, 1028)])
+def test_stream_read_folds_every_word_once(gpu, nbytes, waves):
+    """The bandwidth yardstick reads every 16-byte element exactly once: the XOR of its per-wave words equals
+    the XOR of all 32-bit words of the buffer, for sizes below, equal to and far above one trip of the launch."""
+    torch, mb = gpu
+    rng = np.random.default_rng(nbytes % 1000 + waves)
+    host = rng.integers(0, 2 ** 32, size=nbytes // 4, dtype=np.uint32)
+    src = torch.from_numpy(host.view(np.int32)).to("cuda:0")
+    sink = torch.full((waves,), 0x5A5A5A5A, dtype=torch.int32, device="cuda:0")
+    mb.mdbf_stream_read(src, sink)
+    torch.cuda.synchronize()
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+    assert got == np.bitwise_xor.reduce(host)
+
+
 @pytest.mark.parametrize("m,n,k,l,T", SMALL)
 @pytest.mark.parametrize("precise", [False, True])
 def test_forward_small_shapes(gpu, m, n, k, l, T, precise):
