@@ -185,10 +185,11 @@ def main():
             "scale_in_avg_launch_us": avg_scale_in_ms * 1e3,
             "scale_in_algorithmic_bytes_per_launch": scale_in_bytes_layer * a.copies}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    # the read bandwidth a plain kernel reaches on this device (16-byte loads over 1 GiB, 8 workgroups of 256
-    # lanes per compute unit): the practical ceiling next to the nominal peak
+    # the read bandwidth a plain kernel reaches on this device (non-temporal 16-byte loads over 1 GiB, 2
+    # workgroups of 256 lanes per compute unit, four loads in flight per lane: the best of a sweep): the
+    # practical ceiling next to the nominal peak
     buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
-    sink = torch.zeros(8192, dtype=torch.int32, device="cuda:0")
+    sink = torch.zeros(2048, dtype=torch.int32, device="cuda:0")
     for _ in range(5):
         mb.mdbf_stream_read(buf, sink)
     torch.cuda.synchronize()
