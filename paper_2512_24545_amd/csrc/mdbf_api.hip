@@ -465,9 +465,9 @@ int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t 
     if (h.precise) {
       if (main_k) e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
     } else if (h.mx[st]) {
+      dummy.l = h.mx[st];
       if (pre_k) e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
       if (e) return hip_fail(e);
-      dummy.l = h.mx[st];
       if (main_k) e = launch_stage_mx(items, h.nitems[st], &dummy, s);
     } else if (h.fast[st]) {
       if (h.pre[st] && pre_k) e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);

@@ -93,7 +93,21 @@ __device__ __forceinline__ v6u fp6_encode32(const float (&v)[32], float scale) {
     even[i] = v[2 * i];
     odd[i] = v[2 * i + 1];
   }
-  return __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(even, odd, scale);
+  // The result must not share registers with the sources: with a destination inside the second source's
+  // range the instruction gave wrong limbs (seen in a build whose register allocation produced that
+  // overlap; the compiler's builtin does not exclude it).  Hence the instruction is written out with an
+  // early-clobber result; the idle cycle after it covers the wait a conversion's result may need before
+  // an ordinary vector instruction reads it, which the compiler cannot add around opaque text.
+  v6u out;
+  asm("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, %3\n\ts_nop 1" : "=&v"(out) : "v"(even), "v"(odd), "v"(scale));
+  return out;
+}
+
+// the inverse (32 floats from one limb), with the same precaution
+__device__ __forceinline__ v32f fp6_decode32(v6u limb, float scale) {
+  v32f out;
+  asm("v_cvt_scalef32_pk32_f32_fp6 %0, %1, %2\n\ts_nop 1" : "=&v"(out) : "v"(limb), "v"(scale));
+  return out;
 }
 
 // local column (0..127) of element j (0..31) of lane group kg: element j = 8v + i is nibble i of operand
@@ -149,6 +163,7 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+template <bool RANK8>
 __device__ __forceinline__ void prep_record(const StageProb& p, int unit, int lane, const PrepInput& in, float* pr) {
   const int b = unit / p.KB, q = unit - b * p.KB;
   const int kg = lane >> 4, n = lane & 15;
@@ -174,13 +189,16 @@ __device__ __forceinline__ void prep_record(const StageProb& p, int unit, int la
   }
   wave_lds_sync();
 
-  // ---- 2. gather in operand order, quantise
+  // ---- 2. gather in operand order, quantise.  Rank 8: lanes n and n + 8 both take mode n; the first
+  //         keeps limbs 1 and 3, the second limb 2, so that two matrix-core instructions cover three limbs
+  constexpr bool rank8 = RANK8;   // the launch's rank: every problem of it has l = 8, or every one l = 16
+  const int nsrc = rank8 ? (n & 7) : n;
   float val[32];
   float m = 0.f;
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
     const float presc = (j < 8) ? 2.f : (j < 16 ? 1.f : (j < 24 ? 0.5f : -0.5f));   // undo the nibble values 0.5, 1, 2, -2
-    val[j] = pr[(local_col_of_element(j, 0) + 8 * kg) * kProdStride + n] * presc;
+    val[j] = pr[(local_col_of_element(j, 0) + 8 * kg) * kProdStride + nsrc] * presc;
     m = fmaxf(m, fabsf(val[j]));
   }
   wave_lds_sync();   // the next record's products may overwrite the buffer
@@ -196,16 +214,16 @@ __device__ __forceinline__ void prep_record(const StageProb& p, int unit, int la
   const float sc2 = __builtin_bit_cast(float, (uint32_t)(E + 123) << 23);
   const float sc3 = __builtin_bit_cast(float, (uint32_t)(E + 119) << 23);
   const v6u l1 = fp6_encode32(val, sc1);
-  const v32f b1 = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(l1, sc1);
+  const v32f b1 = fp6_decode32(l1, sc1);
   float r[32];
 #pragma unroll
   for (int j = 0; j < 32; ++j) r[j] = val[j] - b1[j];
   const v6u l2 = fp6_encode32(r, sc2);
-  const v32f b2 = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(l2, sc2);
+  const v32f b2 = fp6_decode32(l2, sc2);
 #pragma unroll
   for (int j = 0; j < 32; ++j) r[j] -= b2[j];
   const v6u l3 = fp6_encode32(r, sc3);
-  const v32f b3 = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(l3, sc3);
+  const v32f b3 = fp6_decode32(l3, sc3);
   // quantised value = val - (last residual); back at the scale of xs, summed over the lane's columns
   float part = 0.f;
 #pragma unroll
@@ -213,18 +231,32 @@ __device__ __forceinline__ void prep_record(const StageProb& p, int unit, int la
     const float inv = (j < 8) ? 0.5f : (j < 16 ? 1.f : 2.f);
     if (j < 24) part += (val[j] - (r[j] - b3[j])) * inv;   // the fourth register's columns need no fix-up
   }
-  const v6u limb[3] = {l1, l2, l3};
+  // record slots: rank 16: limbs 1, 2, 3 of mode n.  Rank 8: slot 0 = limb 1 (n < 8) or limb 2 (n >= 8) of
+  // mode n & 7, slot 1 = limb 3 (n < 8) or zeros, slot 2 unused and not written; each lane's scale bytes
+  // follow its slots.
+  const bool upper = rank8 && n >= 8;
+  v6u slot[3];
+#pragma unroll
+  for (int c = 0; c < 6; ++c) {
+    slot[0][c] = upper ? l2[c] : l1[c];
+    slot[1][c] = rank8 ? (upper ? 0u : l3[c]) : l2[c];
+    slot[2][c] = l3[c];
+  }
+  const uint32_t e0 = (uint32_t)(upper ? E + 123 : E + 127);
+  const uint32_t e1 = (uint32_t)(rank8 ? E + 119 : E + 123);
 #pragma unroll
   for (int L = 0; L < 3; ++L) {
-    u32x4 a;
-    a.x = limb[L][0]; a.y = limb[L][1]; a.z = limb[L][2]; a.w = limb[L][3];
-    u32x2 bpart;
-    bpart.x = limb[L][4]; bpart.y = limb[L][5];
-    ((MDBF_GLOBAL u32x4*)(blk + L * kLimbBytes))[lane] = a;
-    ((MDBF_GLOBAL u32x2*)(blk + L * kLimbBytes + 64 * 16))[lane] = bpart;
+    if (L < 2 || !rank8) {
+      u32x4 a;
+      a.x = slot[L][0]; a.y = slot[L][1]; a.z = slot[L][2]; a.w = slot[L][3];
+      u32x2 bpart;
+      bpart.x = slot[L][4]; bpart.y = slot[L][5];
+      ((MDBF_GLOBAL u32x4*)(blk + L * kLimbBytes))[lane] = a;
+      ((MDBF_GLOBAL u32x2*)(blk + L * kLimbBytes + 64 * 16))[lane] = bpart;
+    }
   }
-  ((MDBF_GLOBAL uint32_t*)(blk + kScaleOff))[lane] =
-      (uint32_t)(E + 127) | ((uint32_t)(E + 123) << 8) | ((uint32_t)(E + 119) << 16);
+  ((MDBF_GLOBAL uint32_t*)(blk + kScaleOff))[lane] = e0 | (e1 << 8) | ((uint32_t)(E + 119) << 16);
+  if (upper) part = 0.f;   // the column sum of a mode is stored once
 
   // ---- 3. column sums of the block
   part += __shfl_xor(part, 16);
@@ -232,6 +264,7 @@ __device__ __forceinline__ void prep_record(const StageProb& p, int unit, int la
   if (lane < 16) ((MDBF_GLOBAL float*)(blk + kColsumOff))[lane] = part;
 }
 
+template <bool RANK8>
 __global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const StageProb* __restrict__ probs,
                                                                       StageProb single, int per_wave) {
   __shared__ __attribute__((aligned(16))) float prod[kPrepWaves][128 * kProdStride];
@@ -249,7 +282,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void mx_scale_in_kernel(const Stag
   for (; unit < end; ++unit) {
     PrepInput next = cur;
     if (unit + 1 < end) next = prep_load(p, unit + 1, lane);
-    prep_record(p, unit, lane, cur, pr);
+    prep_record<RANK8>(p, unit, lane, cur, pr);
     cur = next;
   }
 }
@@ -416,11 +449,13 @@ struct BlockOperands {
   uint32_t w[R];
 };
 
+// NL: record slots the matrix cores contract: 3 (rank 16), 2 (rank 8)
+template <int NL>
 __device__ __forceinline__ BlockOperands read_block(const unsigned char* stage, int blk, int lane, int n, int wave) {
   const unsigned char* rec = stage + blk * kBlockBytes;
   BlockOperands o;
 #pragma unroll
-  for (int L = 0; L < 3; ++L) {
+  for (int L = 0; L < NL; ++L) {
     const u32x4 a = reinterpret_cast<const u32x4*>(rec + L * kLimbBytes)[lane];
     const u32x2 c = reinterpret_cast<const u32x2*>(rec + L * kLimbBytes + 64 * 16)[lane];
     o.limb[L][0] = (int)a.x; o.limb[L][1] = (int)a.y; o.limb[L][2] = (int)a.z; o.limb[L][3] = (int)a.w;
@@ -434,9 +469,10 @@ __device__ __forceinline__ BlockOperands read_block(const unsigned char* stage, 
   return o;
 }
 
-// R tiles of this wave against the block's three limbs.  Tiles past the item's end are contracted too
-// (their sign words repeat the last tile's; the results are not stored): skipping them costs more
-// registers and branches than it saves.
+// R tiles of this wave against the block's limbs.  Tiles past the item's end are contracted too (their
+// sign words repeat the last tile's; the results are not stored): skipping them costs more registers and
+// branches than it saves.
+template <int NL>
 __device__ __forceinline__ void contract_block(const BlockOperands& o, floatx4 (&acc)[R], float& colsum,
                                                const SignConsts& k) {
   colsum += o.colsum;
@@ -445,7 +481,7 @@ __device__ __forceinline__ void contract_block(const BlockOperands& o, floatx4 (
   for (int r = 0; r < R; ++r) a[r] = sign_operand(o.w[r], k);
   // limb outermost: consecutive instructions write different accumulators
 #pragma unroll
-  for (int L = 0; L < 3; ++L) {
+  for (int L = 0; L < NL; ++L) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       acc[r] = mx_mfma(a[r], o.limb[L], acc[r], L, o.scales);
@@ -521,8 +557,10 @@ __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, 
   }
 }
 
-// RANK: the envelope rank of every problem of the launch, 16 or 8 (the matrix-core tile is 16 modes wide
-// either way; with 8 the activation records carry zeros in modes 8..15).
+// RANK: the envelope rank of every problem of the launch, 16 or 8.  The matrix-core tile is 16 columns wide
+// either way; with rank 8, column n < 8 carries limbs 1 and 3 of mode n and column n + 8 limb 2 of the same
+// mode (each column has its own scales), so a tile and block take two instructions instead of three; the
+// sum over the 16 columns in the epilogue, with mode n's envelope entry on both of its columns, joins them.
 template <bool BATCH, int RANK>
 __global__ __launch_bounds__(kThreads)
 void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single) {
@@ -575,8 +613,9 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
 #pragma unroll
         for (int blk = 0; blk < SB; ++blk) {
           if (t * SB + blk < it.KB) {
-            const BlockOperands o = read_block(stage, blk, lane, n, wave);
-            contract_block(o, acc, colsum, sconst);
+            constexpr int kSlots = RANK == 8 ? 2 : 3;
+            const BlockOperands o = read_block<kSlots>(stage, blk, lane, n, wave);
+            contract_block<kSlots>(o, acc, colsum, sconst);
           }
         }
       }
@@ -592,7 +631,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
             float v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const float ev = (RANK == 16 || n < RANK) ? (float)eoh[(trel * kTileRows + 4 * kg + i) * RANK + (n & (RANK - 1))] : 0.f;
+              const float ev = (float)eoh[(trel * kTileRows + 4 * kg + i) * RANK + (n & (RANK - 1))];
               const float P = colsum - 2.f * acc[r][i];
               v[i] = row16_sum(ev * P);
             }
@@ -644,8 +683,12 @@ int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, con
   per_wave = per_wave < 1 ? 1 : per_wave > mx::kPrepMaxPerWave ? mx::kPrepMaxPerWave : per_wave;
   const int waves = (max_units + (int)per_wave - 1) / (int)per_wave;
   const int wgs = (waves + mx::kPrepWaves - 1) / mx::kPrepWaves;
-  hipLaunchKernelGGL(mx::mx_scale_in_kernel, dim3((unsigned)wgs, (unsigned)count), dim3(64 * mx::kPrepWaves), 0, s,
-                     probs_dev, *single, (int)per_wave);
+  if (single->l == 8)
+    hipLaunchKernelGGL(mx::mx_scale_in_kernel<true>, dim3((unsigned)wgs, (unsigned)count), dim3(64 * mx::kPrepWaves),
+                       0, s, probs_dev, *single, (int)per_wave);
+  else
+    hipLaunchKernelGGL(mx::mx_scale_in_kernel<false>, dim3((unsigned)wgs, (unsigned)count), dim3(64 * mx::kPrepWaves),
+                       0, s, probs_dev, *single, (int)per_wave);
   return (int)hipGetLastError();
 }
 

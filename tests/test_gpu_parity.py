@@ -171,8 +171,8 @@ def test_block_scaled_shapes(gpu, m, n, k, T):
 
 @pytest.mark.parametrize("m,n,k,T", [(40, 300, 70, 2), (1100, 1030, 2105, 1), (4096, 4096, 1856, 1), (2064, 520, 4100, 16)])
 def test_block_scaled_rank_8(gpu, m, n, k, T):
-    """Rank-8 envelopes (the 1.0 bits-per-weight budget) through the block-scaled kernel: modes 8..15 of the
-    16-wide matrix-core tile are fed zeros."""
+    """Rank-8 envelopes (the 1.0 bits-per-weight budget) through the block-scaled kernel: the 16-wide
+    matrix-core tile carries two limbs of every mode side by side."""
     L = synth.make_layer(m, n, k, 8, seed=m + 3 * n + 5 * k + 8, env_dtype="f16", env_kind="unit", signed_env=True)
     X = synth.make_activations(n, T, seed=78 + m, x_dtype="f16")
     ref = orc.forward_factored(*_oracle_args(L), X)
