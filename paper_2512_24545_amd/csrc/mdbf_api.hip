@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "mdbf_internal.h"
@@ -267,6 +268,43 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
   return MDBF_OK;
 }
 
+// Work items of a stage of the block-scaled kernel, reordered for its static schedule.  The kernel's
+// workgroups (nwg of them; groups of nwg / 8 per XCD when nwg is a multiple of 8) walk a contiguous slice
+// [lo, hi) of the table: workgroup j of the slice takes entries lo + j, lo + j + stride, ...  An item costs
+// its stage count (tokens x (ceil(KB / 2) + 1)), whatever its tile count; with problems of different
+// contraction lengths in one plan the slices' workgroups would end at very different times.  Within each
+// slice: items in descending cost (ties keep their order), dealt round by round, the costliest of a round
+// to the workgroup with the least so far (ties: lowest index).  Slices whose items all cost the same keep
+// their order.
+static void balance_mx_items(WorkItem* items, int n, int max_wgs) {
+  const int nwg = n < max_wgs ? n : max_wgs;
+  const int slices = (nwg & 7) == 0 ? 8 : 1;
+  const int stride = nwg / slices;
+  if (stride < 1) return;
+  std::vector<WorkItem> sorted;
+  std::vector<long> load((size_t)stride);
+  std::vector<int> order((size_t)stride);
+  for (int x = 0; x < slices; ++x) {
+    const int lo = (int)(((long)n * x) / slices), hi = (int)(((long)n * (x + 1)) / slices);
+    auto cost = [](const WorkItem& w) { return (long)w.p.T * ((w.p.KB + 1) / 2 + 1); };
+    sorted.assign(items + lo, items + hi);
+    std::stable_sort(sorted.begin(), sorted.end(),
+                     [&](const WorkItem& a, const WorkItem& b) { return cost(a) > cost(b); });
+    std::fill(load.begin(), load.end(), 0L);
+    for (int base = 0; base < hi - lo; base += stride) {
+      const int cnt = (hi - lo - base) < stride ? (hi - lo - base) : stride;   // workgroups 0 .. cnt - 1 take part
+      for (int j = 0; j < cnt; ++j) order[(size_t)j] = j;
+      std::stable_sort(order.begin(), order.begin() + cnt,
+                       [&](int a, int b) { return load[(size_t)a] < load[(size_t)b]; });
+      for (int r = 0; r < cnt; ++r) {
+        const int j = order[(size_t)r];
+        items[lo + base + j] = sorted[(size_t)(base + r)];
+        load[(size_t)j] += cost(sorted[(size_t)(base + r)]);
+      }
+    }
+  }
+}
+
 static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, size_t* ws_bytes) {
   if (count < 1 || !layers) return MDBF_EINVAL;
   long tiles[2] = {0, 0};
@@ -402,6 +440,8 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
       }
     }
   }
+  for (int s = 0; s < 2; ++s)
+    if (h.mx[s] && !h.precise && !h.gemm) balance_mx_items(items[s], ni[s], mx_max_workgroups());
   h.fast[0] = fast[0];
   h.fast[1] = fast[1];
   h.pre[0] = fast[0] && pre[0];
