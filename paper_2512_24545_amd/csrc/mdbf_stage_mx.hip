@@ -54,7 +54,7 @@ constexpr int kBlockBytes = 5120;              // padded to a multiple of 1 KB (
 #define MDBF_MX_WAVES 8
 #endif
 constexpr int kComputeWaves = MDBF_MX_WAVES;
-constexpr int R = 8;                                   // row tiles per contraction wave
+constexpr int R = 64 / kComputeWaves;                  // row tiles per contraction wave
 constexpr int kItemTiles = kComputeWaves * R;          // row tiles per work item
 static_assert(kGroupTiles % kItemTiles == 0, "an item lies inside one group of the packed layout");
 constexpr int SB = 2;                                  // blocks per stage
@@ -69,7 +69,7 @@ constexpr int kSignInstr = kStageSigns / 1024;
 constexpr int kEoInstr = kEoBytes / 1024;
 constexpr int kSmemBytes = kStages * kStageBytes;
 constexpr int kWgsPerCu = (160 * 1024) / kSmemBytes;   // workgroups of this kernel a compute unit holds
-constexpr int kLoaderWaves = kComputeWaves / 4;        // a wave keeps at most 63 loads in flight
+constexpr int kLoaderWaves = 2;                        // a wave keeps at most 63 loads in flight
 constexpr int kThreads = 64 * (kComputeWaves + kLoaderWaves);
 static_assert(kXsInstr % kLoaderWaves == 0 && kSignInstr % kLoaderWaves == 0 && kEoInstr % kLoaderWaves == 0,
               "the loader waves split every stage evenly");
@@ -476,15 +476,19 @@ template <int NL>
 __device__ __forceinline__ void contract_block(const BlockOperands& o, floatx4 (&acc)[R], float& colsum,
                                                const SignConsts& k) {
   colsum += o.colsum;
-  v8i a[R];
+  // eight tiles at a time (their expanded sign operands are 32 registers), limb outermost: consecutive
+  // instructions write different accumulators
 #pragma unroll
-  for (int r = 0; r < R; ++r) a[r] = sign_operand(o.w[r], k);
-  // limb outermost: consecutive instructions write different accumulators
+  for (int h = 0; h < R; h += 8) {
+    v8i a[8];
 #pragma unroll
-  for (int L = 0; L < NL; ++L) {
+    for (int r = 0; r < 8; ++r) a[r] = sign_operand(o.w[h + r], k);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      acc[r] = mx_mfma(a[r], o.limb[L], acc[r], L, o.scales);
+    for (int L = 0; L < NL; ++L) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        acc[h + r] = mx_mfma(a[r], o.limb[L], acc[h + r], L, o.scales);
+      }
     }
   }
 }
