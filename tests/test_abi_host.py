@@ -151,6 +151,94 @@ def test_batch_plan_errors_and_sizes():
     assert L.mdbf_forward_batch(bad, FAKE, 4096, None) == -1
 
 
+class _StageProb(C.Structure):
+    # mirror of the library's internal stage descriptor (white-box: the plan is a byte blob of the library)
+    _fields_ = [("S", C.c_void_p), ("Ein", C.c_void_p), ("Eout", C.c_void_p), ("vin", C.c_void_p),
+                ("out", C.c_void_p), ("xs", C.c_void_p), ("vin_ld", C.c_int64), ("out_ld", C.c_int64),
+                ("rows", C.c_int32), ("K", C.c_int32), ("l", C.c_int32), ("T", C.c_int32),
+                ("KB", C.c_int32), ("ntiles", C.c_int32), ("env_dt", C.c_int32), ("vin_dt", C.c_int32),
+                ("out_dt", C.c_int32), ("flags", C.c_int32)]
+
+
+class _WorkItem(C.Structure):
+    _fields_ = [("p", _StageProb), ("tile0", C.c_int32), ("ntiles", C.c_int32), ("prob", C.c_int32),
+                ("pad", C.c_int32), ("fill", C.c_uint8 * 8)]
+
+
+class _PlanHeader(C.Structure):
+    _fields_ = [("magic", C.c_uint32), ("count", C.c_int32), ("nitems", C.c_int32 * 2),
+                ("tiles_per_item", C.c_int32 * 2), ("precise", C.c_int32), ("fast", C.c_int32 * 2),
+                ("pre", C.c_int32 * 2), ("max_units", C.c_int32 * 2), ("mx", C.c_int32 * 2), ("gemm", C.c_int32),
+                ("gemm_mode", C.c_int32 * 2), ("max_tokens", C.c_int32), ("max_units_mx", C.c_int32 * 2),
+                ("probs_off", C.c_uint64 * 2), ("items_off", C.c_uint64 * 2), ("total_bytes", C.c_uint64)]
+
+
+def _plan_items(shapes, T=1):
+    """Builds a plan of rank-16 fp16 layers over placeholder pointers (plan building touches no device
+    memory) and returns its header and the two work-item tables."""
+    L = mb.lib()
+    n = len(shapes)
+    arr = (mb.Layer * n)()
+    for i, (m, nn, k) in enumerate(shapes):
+        arr[i].desc = mb.Desc(m, nn, k, 16, 0, 0, 0, 0)
+        arr[i].SA_packed_dev = FAKE
+        arr[i].SB_packed_dev = FAKE
+        arr[i].env = mb.Env(FAKE, FAKE, FAKE, FAKE)
+        arr[i].X_dev = FAKE
+        arr[i].ldx = nn
+        arr[i].Y_dev = FAKE
+        arr[i].ldy = m
+        arr[i].T = T
+    pb, wb = C.c_size_t(0), C.c_size_t(0)
+    assert L.mdbf_batch_plan_bytes(n, arr, C.byref(pb), C.byref(wb)) == 0
+    buf = C.create_string_buffer(pb.value)
+    assert L.mdbf_batch_plan_build(n, arr, FAKE, wb.value, buf, pb.value) == 0
+    assert C.sizeof(_StageProb) == 104 and C.sizeof(_WorkItem) == 128
+    h = _PlanHeader.from_buffer_copy(buf.raw[:C.sizeof(_PlanHeader)])
+    tables = []
+    for s in range(2):
+        off = h.items_off[s]
+        tables.append([_WorkItem.from_buffer_copy(buf.raw[off + 128 * i: off + 128 * (i + 1)])
+                       for i in range(h.nitems[s])])
+    return h, tables
+
+
+def test_block_scaled_plan_schedule_is_a_balanced_permutation():
+    """Host logic of mdbf_batch_plan_build for the block-scaled kernel: the work items of a stage are the
+    64-tile cuts of every problem, each exactly once, and within each of the eight slices of the table the 32
+    workgroups (entry j, j + 32, ...) carry stage counts that differ by at most one item's."""
+    attn, down = (4096, 4096, 2656), (4096, 11008, 4096)
+    shapes = [attn, down] * 40                       # contraction lengths of 32 and 86 blocks in stage 1
+    h, tables = _plan_items(shapes)
+    assert h.magic == 0x4D444246 and h.count == 80 and list(h.mx) == [16, 16] and h.gemm == 0
+    for s, items in enumerate(tables):
+        want = []
+        for i, (m, nn, k) in enumerate(shapes):
+            rows = k if s == 0 else m
+            nt = (rows + 15) // 16
+            want += [(i, t0, min(64, nt - t0)) for t0 in range(0, nt, 64)]
+        got = [(w.prob, w.tile0, w.ntiles) for w in items]
+        assert sorted(got) == sorted(want) and len(got) == len(want)
+        n, stride = len(items), 32
+        assert n >= 256
+        cost = lambda w: w.p.T * ((w.p.KB + 1) // 2 + 1)
+        for x in range(8):
+            lo, hi = n * x // 8, n * (x + 1) // 8
+            loads = [sum(cost(items[i]) for i in range(lo + j, hi, stride)) for j in range(stride)]
+            assert max(loads) - min(loads) <= max(cost(w) for w in items[lo:hi])
+    # stage 1 mixes 17-stage and 44-stage items: in problem order one workgroup would carry two long ones
+    c1 = sorted({tables[0][i].p.KB for i in range(len(tables[0]))})
+    assert c1 == [32, 86]
+
+
+def test_block_scaled_plan_of_equal_layers_keeps_problem_order():
+    h, tables = _plan_items([(4096, 4096, 2656)] * 100)
+    assert list(h.mx) == [16, 16]
+    for items in tables:
+        got = [(w.prob, w.tile0) for w in items]
+        assert got == sorted(got)
+
+
 def test_strerror():
     L = mb.lib()
     assert L.mdbf_strerror(0) == b"ok"
