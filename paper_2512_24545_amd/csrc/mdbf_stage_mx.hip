@@ -465,7 +465,7 @@ __device__ __forceinline__ BlockOperands read_block(const unsigned char* stage, 
   o.colsum = reinterpret_cast<const float*>(rec + kColsumOff)[n];
   const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage + kStageXs) + blk * kItemTiles * 64 + lane;
 #pragma unroll
-  for (int r = 0; r < R; ++r) o.w[r] = sw[(wave + kComputeWaves * r) * 64];
+  for (int r = 0; r < R; ++r) o.w[r] = sw[(wave * R + r) * 64];
   return o;
 }
 
@@ -602,7 +602,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   ItemInfo it = load_item<BATCH>(items, single, item);
   int slot = 0;
   for (;;) {
-    const int nr = min(R, (it.ntl - wave + kComputeWaves - 1) / kComputeWaves);   // valid tiles of this wave
+    const int nr = max(0, min(R, it.ntl - wave * R));   // valid tiles of this wave (it owns tiles wave * R ..)
     for (int b = 0; b < it.T; ++b) {
       floatx4 acc[R];
 #pragma unroll
@@ -616,7 +616,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
         slot = (slot + 1 == kStages) ? 0 : slot + 1;
 #pragma unroll
         for (int blk = 0; blk < SB; ++blk) {
-          if (t * SB + blk < it.KB) {
+          if (t * SB + blk < it.KB && nr > 0) {   // (a wave past the item's end only keeps the barriers)
             constexpr int kSlots = RANK == 8 ? 2 : 3;
             const BlockOperands o = read_block<kSlots>(stage, blk, lane, n, wave);
             contract_block<kSlots>(o, acc, colsum, sconst);
@@ -631,7 +631,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           if (r < nr) {
-            const int trel = wave + kComputeWaves * r;
+            const int trel = wave * R + r;
             float v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
