@@ -454,6 +454,31 @@ def test_decoder_stack_layer_through_batch(gpu, budget, T):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
 
 
+def test_block_scaled_plan_with_more_items_than_workgroups(gpu):
+    """300 small problems of mixed contraction lengths in one block-scaled plan: more work items than the
+    device holds workgroups, so that the host's cost-balanced item order and the kernel's walk over several
+    items per workgroup are both on the path; every problem is compared with the oracle."""
+    torch, mb = gpu
+    rng = np.random.default_rng(31)
+    layers, Xs, Ys, refs = [], [], [], []
+    for i in range(300):
+        m = int(rng.integers(17, 80))
+        n = int(rng.choice([256, 300, 640, 1280]))
+        k = int(rng.choice([130, 256, 640]))
+        L = synth.make_layer(m, n, k, 16, seed=7000 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+        X = synth.make_activations(n, 1, seed=8000 + i, x_dtype="f16")
+        layers.append(mb.DeviceLayer.from_host(L))
+        Xs.append(_to_dev(torch, X, "f16"))
+        Ys.append(torch.zeros((1, m), dtype=torch.float32, device="cuda:0"))
+        refs.append(orc.forward_factored(*_oracle_args(L), X))
+    plan = mb.BatchPlan(layers, Xs, Ys, block_scaled=True)
+    for _ in range(2):                      # the plan is reusable
+        plan.run()
+    torch.cuda.synchronize()
+    for Yb, ref in zip(Ys, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
+
+
 # ---------------------------------------------------------------- factors with the structure of a quantisation run
 @pytest.mark.parametrize("rows,cols,R,l,outer", [(320, 288, 96, 4, 1), (272, 400, 160, 16, 0), (272, 400, 160, 16, 2)])
 @pytest.mark.parametrize("variant", ["auto", "block_scaled", "tokens", "precise"])
