@@ -680,9 +680,9 @@ static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* sing
 }  // namespace mx
 
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single, hipStream_t s) {
-  // records per wave: as many as it takes for the launch to be resident at once (four workgroups per
-  // compute unit: their LDS), so that a wave's memory round trips overlap its own arithmetic
-  const long resident = (long)compute_units() * 4 * mx::kPrepWaves;
+  // records per wave: as many as it takes for the launch to be resident at once (three workgroups per
+  // compute unit: their registers), so that a wave's memory round trips overlap its own arithmetic
+  const long resident = (long)compute_units() * 3 * mx::kPrepWaves;
   long per_wave = ((long)count * max_units + resident - 1) / resident;
   per_wave = per_wave < 1 ? 1 : per_wave > mx::kPrepMaxPerWave ? mx::kPrepMaxPerWave : per_wave;
   const int waves = (max_units + (int)per_wave - 1) / (int)per_wave;
