@@ -270,12 +270,13 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
 
 // Work items of a stage of the block-scaled kernel, reordered for its static schedule.  The kernel's
 // workgroups (nwg of them; groups of nwg / 8 per XCD when nwg is a multiple of 8) walk a contiguous slice
-// [lo, hi) of the table: workgroup j of the slice takes entries lo + j, lo + j + stride, ...  An item costs
-// its stage count (tokens x (ceil(KB / 2) + 1)), whatever its tile count; with problems of different
-// contraction lengths in one plan the slices' workgroups would end at very different times.  Within each
-// slice: items in descending cost (ties keep their order), dealt round by round, the costliest of a round
-// to the workgroup with the least so far (ties: lowest index).  Slices whose items all cost the same keep
-// their order.
+// [lo, hi) of the table: workgroup j of the slice takes entries lo + j, lo + j + stride, ..., so the first
+// (hi - lo) mod stride workgroups take one entry more than the others.  An item costs its stage count
+// (tokens x (ceil(KB / 2) + 1)), whatever its tile count; with problems of different contraction lengths in
+// one plan the slice's workgroups would end at very different times.  Within each slice: items in
+// descending cost (ties keep their order), each to the workgroup with the least cost so far among those
+// with a free entry (ties: the one with fewer entries in all, then the lowest index), so that the costliest
+// items land where fewer items go.  Slices whose items all cost the same keep their order.
 static void balance_mx_items(WorkItem* items, int n, int max_wgs) {
   const int nwg = n < max_wgs ? n : max_wgs;
   const int slices = (nwg & 7) == 0 ? 8 : 1;
@@ -283,24 +284,32 @@ static void balance_mx_items(WorkItem* items, int n, int max_wgs) {
   if (stride < 1) return;
   std::vector<WorkItem> sorted;
   std::vector<long> load((size_t)stride);
-  std::vector<int> order((size_t)stride);
+  std::vector<int> cap((size_t)stride), used((size_t)stride);
+  auto cost = [](const WorkItem& w) { return (long)w.p.T * ((w.p.KB + 1) / 2 + 1); };
   for (int x = 0; x < slices; ++x) {
     const int lo = (int)(((long)n * x) / slices), hi = (int)(((long)n * (x + 1)) / slices);
-    auto cost = [](const WorkItem& w) { return (long)w.p.T * ((w.p.KB + 1) / 2 + 1); };
+    const int cnt = hi - lo;
+    if (cnt < 2) continue;
     sorted.assign(items + lo, items + hi);
     std::stable_sort(sorted.begin(), sorted.end(),
                      [&](const WorkItem& a, const WorkItem& b) { return cost(a) > cost(b); });
-    std::fill(load.begin(), load.end(), 0L);
-    for (int base = 0; base < hi - lo; base += stride) {
-      const int cnt = (hi - lo - base) < stride ? (hi - lo - base) : stride;   // workgroups 0 .. cnt - 1 take part
-      for (int j = 0; j < cnt; ++j) order[(size_t)j] = j;
-      std::stable_sort(order.begin(), order.begin() + cnt,
-                       [&](int a, int b) { return load[(size_t)a] < load[(size_t)b]; });
-      for (int r = 0; r < cnt; ++r) {
-        const int j = order[(size_t)r];
-        items[lo + base + j] = sorted[(size_t)(base + r)];
-        load[(size_t)j] += cost(sorted[(size_t)(base + r)]);
+    if (cost(sorted.front()) == cost(sorted.back())) continue;
+    for (int j = 0; j < stride; ++j) {
+      cap[(size_t)j] = (cnt - j + stride - 1) / stride;   // entries lo + j + k * stride below hi
+      used[(size_t)j] = 0;
+      load[(size_t)j] = 0;
+    }
+    for (int i = 0; i < cnt; ++i) {
+      int best = -1;
+      for (int j = 0; j < stride; ++j) {
+        if (used[(size_t)j] >= cap[(size_t)j]) continue;
+        if (best < 0 || load[(size_t)j] < load[(size_t)best] ||
+            (load[(size_t)j] == load[(size_t)best] && cap[(size_t)j] < cap[(size_t)best]))
+          best = j;
       }
+      items[lo + best + used[(size_t)best] * stride] = sorted[(size_t)i];
+      ++used[(size_t)best];
+      load[(size_t)best] += cost(sorted[(size_t)i]);
     }
   }
 }

@@ -231,6 +231,23 @@ def test_block_scaled_plan_schedule_is_a_balanced_permutation():
     assert c1 == [32, 86]
 
 
+def test_block_scaled_plan_puts_long_items_where_fewer_items_go():
+    """96 MLP projections: factor 1 has 384 items on 256 workgroups (48 per slice: the first 16 workgroups of
+    a slice take two, the others one); 16 items of a slice are 44 stages long (contraction over 11008), 32 are
+    17.  The long ones must go alone: no workgroup carries more than 44 stages."""
+    shapes = [(11008, 4096, 4096), (11008, 4096, 4096), (4096, 11008, 4096)] * 32
+    h, tables = _plan_items(shapes)
+    assert list(h.mx) == [16, 16]
+    items = tables[0]
+    assert len(items) == 384
+    cost = lambda w: w.p.T * ((w.p.KB + 1) // 2 + 1)
+    assert sorted({cost(w) for w in items}) == [17, 44]
+    for x in range(8):
+        lo, hi = 48 * x, 48 * (x + 1)
+        loads = [sum(cost(items[i]) for i in range(lo + j, hi, 32)) for j in range(32)]
+        assert max(loads) == 44 and min(loads) == 34
+
+
 def test_block_scaled_plan_of_equal_layers_keeps_problem_order():
     h, tables = _plan_items([(4096, 4096, 2656)] * 100)
     assert list(h.mx) == [16, 16]
