@@ -24,7 +24,10 @@ Readings of the paper taken here:
     the test matrices falls sweep after sweep; far below, the sign-adaptive step undoes the fit.
 
 Parity status: every function is pinned by tests/test_quantizer_pins.py (Theorem 1's closed-form error,
-Eckart-Young for the initialisation, fixed points, first-order optimality of the least-squares step).
+Eckart-Young for the initialisation, fixed points, first-order optimality of the least-squares step; the
+refinement loop over several inner iterations and one full outer sweep against the three update
+equations retyped with bare numpy calls, with planted mistakes -- a flipped dual update, a prox without
+the dual variable, no U / V alternation -- shown to be caught).
 """
 from __future__ import annotations
 

@@ -143,3 +143,63 @@ def test_more_envelope_modes_fit_better_and_refinement_helps():
     e0 = qz.relative_error(W, _what(qz.quantize(W, R=40, l=4, outer=0)))
     e3 = qz.relative_error(W, _what(qz.quantize(W, R=40, l=4, outer=3)))
     assert e3 < e0
+
+
+# ---- the refinement loop beyond its first iteration, and the U / V alternation, retyped with bare numpy
+def _bare_msvid(Z, l):
+    """sign(Z) o TSVD_l(|Z|) (Eq. "msvid-def") with numpy calls only; sign(0) = +1."""
+    Uf, s, Vt = np.linalg.svd(np.abs(Z), full_matrices=False)
+    return np.where(Z < 0, -1.0, 1.0) * ((Uf[:, :l] * s[:l]) @ Vt[:l, :])
+
+
+def _bare_refine(W, U, V, l, rho, inner, dual_sign=+1.0, lam_in_prox=True):
+    """Eqs. "admm-U-tilde", "admm-U-prox", "admm-U-dual" written out, dual variable starting at zero.
+    dual_sign / lam_in_prox plant the two mistakes the pin must catch."""
+    R = V.shape[1]
+    Lam = np.zeros_like(U)
+    for _ in range(inner):
+        Ut = (W @ V + rho * (U - Lam)) @ np.linalg.inv(V.T @ V + rho * np.eye(R))
+        U = _bare_msvid(Ut + (Lam if lam_in_prox else 0.0), l)
+        Lam = Lam + dual_sign * (Ut - U)
+    return U
+
+
+@pytest.mark.parametrize("l,inner", [(1, 2), (2, 2), (2, 3)])
+def test_refine_factor_by_hand_beyond_the_first_iteration(l, inner):
+    rng = np.random.default_rng(40 + l + inner)
+    W = _mat(41, 6, 5)
+    R, rho = 3, 0.8
+    U_start = _bare_msvid(rng.standard_normal((6, R)), l)      # a member of the format: the loop's own input form
+    V = rng.standard_normal((5, R))
+    # the oracle takes the factor as (S, A, Q): hand it the same matrix through its own parametrisation
+    S0 = np.where(U_start < 0, -1, 1).astype(np.int8)
+    Uf, s, Vt = np.linalg.svd(np.abs(U_start), full_matrices=False)
+    fU = (S0, Uf[:, :l] * np.sqrt(s[:l]), Vt[:l, :].T * np.sqrt(s[:l]))
+    np.testing.assert_allclose(S0 * (fU[1] @ fU[2].T), U_start, atol=1e-12)
+    S, A, Q = qz.refine_factor(W, fU, V, l, rho, inner)
+    want = _bare_refine(W, U_start, V, l, rho, inner)
+    np.testing.assert_allclose(S * (A @ Q.T), want, rtol=1e-9, atol=1e-10)
+    # the pin has teeth: a flipped dual update, or a prox without the dual variable, gives another matrix
+    for kw in (dict(dual_sign=-1.0), dict(lam_in_prox=False)):
+        wrong = _bare_refine(W, U_start, V, l, rho, inner, **kw)
+        assert np.abs(wrong - want).max() > 1e-4 * np.abs(want).max(), kw
+
+
+def test_quantize_one_outer_sweep_by_hand():
+    """Initialisation, then U refined against the initial V, then V refined against the new U on the
+    transposed problem (Sec. 4.3.2), rho = rho_rel * trace(V^T V) / R of the fixed factor."""
+    W = _mat(43, 6, 5)
+    R, l, inner, rho_rel = 3, 2, 2, 1.5
+    Uf, s, Vt = np.linalg.svd(W, full_matrices=False)
+    U = _bare_msvid(Uf[:, :R] * np.sqrt(s[:R]), l)
+    V = _bare_msvid(Vt[:R, :].T * np.sqrt(s[:R]), l)
+    U = _bare_refine(W, U, V, l, rho_rel * np.trace(V.T @ V) / R, inner)
+    V_new = _bare_refine(W.T, V, U, l, rho_rel * np.trace(U.T @ U) / R, inner)
+    L = qz.quantize(W, R, l, rho_rel=rho_rel, outer=1, inner=inner)
+    np.testing.assert_allclose(orc.factor_U(L["SA"], L["A"], L["Q"]), U, rtol=1e-9, atol=1e-10)
+    np.testing.assert_allclose(orc.factor_V(L["SB"], L["G"], L["B"]), V_new.T, rtol=1e-9, atol=1e-10)
+    np.testing.assert_allclose(_what(L), U @ V_new.T, rtol=1e-9, atol=1e-10)
+    # planted mistake: V refined against the OLD U (no alternation) is a different layer
+    U_old = _bare_msvid(Uf[:, :R] * np.sqrt(s[:R]), l)
+    V_stale = _bare_refine(W.T, V, U_old, l, rho_rel * np.trace(U_old.T @ U_old) / R, inner)
+    assert np.abs(V_stale - V_new).max() > 1e-4 * np.abs(V_new).max()
