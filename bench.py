@@ -29,6 +29,13 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0
 
+# the arithmetic of the one-token product kernels (inputs, envelopes and outputs are fp16 either way)
+DTYPE_OF_KERNEL = {
+    "stage_mx_kernel": "fp4 signs x fp6 limbs (3 per activation, power-of-two scale per 32: block-floating, "
+                       "~13 bits of the block maximum), f32 accumulate; f16 in/out",
+    "stage_fast_kernel": "f16 x f16, f32 accumulate",
+}
+
 M, N, K, L = 4096, 4096, 2656, 16
 
 
@@ -61,9 +68,28 @@ def make_device_layers(torch, mb, copies, seed):
     return layers, Xs, Ys
 
 
+def preheat(torch, fn, min_ms=150.0):
+    """Run fn() back to back for at least min_ms of GPU time: the shader clock needs some 50 ms of sustained
+    load to settle, whatever the counted warm-up says.  Returns the milliseconds spent."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    total, batch = 0.0, 8
+    while total < min_ms:
+        e0.record()
+        for _ in range(batch):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        dt = e0.elapsed_time(e1)
+        total += dt
+        # aim at batches of about 30 ms so that the check costs little idle time
+        batch = max(batch, min(4096, int(batch * 30.0 / max(dt, 1e-3))))
+    return total
+
+
 def oracle_check(torch, mb, layer, X, Y):
     """Download one layer (logical signs through mdbf_unpack) and compare with the CPU oracle."""
     from oracle import mdbf_oracle as orc
+    M, N, K = layer.m, layer.n, layer.k
     SA = mb.mdbf_unpack(layer.SA_packed, M, K).cpu().numpy()
     SB = mb.mdbf_unpack(layer.SB_packed, K, N).cpu().numpy()
     args = (SA, SB, layer.A.float().cpu().numpy(), layer.Q.float().cpu().numpy(),
@@ -72,26 +98,35 @@ def oracle_check(torch, mb, layer, X, Y):
     return orc.max_rel_error(Y.float().cpu().numpy(), ref), args
 
 
-def cpu_baseline(args, X, budget_s=12.0):
-    """The oracle's factored forward, as it stands, on the host cores."""
+def cpu_baseline(args, X, budget_s=8.0):
+    """The oracle's factored forward, as it stands (numpy fp64; its matrix products run in the BLAS numpy is
+    linked with), on the host: once with all the threads that BLAS takes and once limited to one."""
     from oracle import mdbf_oracle as orc
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+    from threadpoolctl import threadpool_info, threadpool_limits
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     Xh = X.float().cpu().numpy()
-    orc.forward_factored(*args, Xh)
-    t0 = time.perf_counter()
-    calls = 0
-    while True:
+
+    def timed(budget, max_calls):
         orc.forward_factored(*args, Xh)
-        calls += 1
-        if time.perf_counter() - t0 > budget_s or calls >= 200:
-            break
-    dt = (time.perf_counter() - t0) / calls
-    return {"value": algorithmic_bytes(M, N, K, L) / dt / 1e9, "unit": "GB/s", "cores": int(cores),
+        t0 = time.perf_counter()
+        calls = 0
+        while True:
+            orc.forward_factored(*args, Xh)
+            calls += 1
+            if time.perf_counter() - t0 > budget or calls >= max_calls:
+                break
+        return (time.perf_counter() - t0) / calls, calls
+
+    dt, calls = timed(budget_s, 200)
+    with threadpool_limits(limits=1):
+        dt1, calls1 = timed(budget_s, 60)
+    nbytes = algorithmic_bytes(M, N, K, L)
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": int(cores),
             "kind": "oracle", "ms_per_call": dt * 1e3,
+            "one_core": {"value": nbytes / dt1 / 1e9, "unit": "GB/s", "cores": 1, "ms_per_call": dt1 * 1e3,
+                         "calls": calls1},
+            "implementation": "numpy fp64, factored order (H1-H5), sign matrices as int8 converted per call; "
+                              "threads are the BLAS pool's, not OpenMP loops over rows",
             "sample": "%d forward calls of the numpy fp64 oracle (factored order) on one 4096x4096 k=2656 l=16 layer"
                       % calls}
 
@@ -99,10 +134,12 @@ def cpu_baseline(args, X, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # the shader clock takes some 50 ms of sustained load to settle: a few dozen steps (0.3 ms each) are
-    # measured at a lower clock than the steady state the figure is meant to describe
+    # the shader clock takes some 50 ms of sustained load to settle; every timed loop below is preceded by a
+    # time-based preheat, so that a few dozen steps (0.3 ms each) measure the same state as a few thousand
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
+    ap.add_argument("--preheat-ms", type=float, default=150.0,
+                    help="GPU time of untimed load before the counted warm-up (clock settling)")
     ap.add_argument("--copies", type=int, default=336, help="independent layers per step (336 x 3.17 MB > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the graph / hot / latency side measurements")
@@ -135,7 +172,8 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    # ---- the timed region: K steps of the batched path
+    # ---- the timed region: K steps of the batched path, after a time-based preheat and the W counted steps
+    preheat_ms = preheat(torch, plan.run, a.preheat_ms)
     for _ in range(a.warmup):
         plan.run()
     torch.cuda.synchronize()
@@ -154,19 +192,22 @@ def main():
 
     # ---- roofline of the dominant kernel: the product kernel (one launch per factor, two per step), timed
     #      by itself over the same number of steps; the scale-in results of the last full step stay valid
+    part_steps = max(a.steps, 200)
     e0, e1 = ev(), ev()
+    preheat(torch, lambda: plan.run_part(3, 2), a.preheat_ms)
     e0.record()
-    for _ in range(a.steps):
+    for _ in range(part_steps):
         plan.run_part(3, 2)
     e1.record()
     torch.cuda.synchronize()
-    avg_launch_ms = e0.elapsed_time(e1) / (2 * a.steps)
+    avg_launch_ms = e0.elapsed_time(e1) / (2 * part_steps)
+    preheat(torch, lambda: plan.run_part(3, 1), a.preheat_ms)
     e0.record()
-    for _ in range(a.steps):
+    for _ in range(part_steps):
         plan.run_part(3, 1)
     e1.record()
     torch.cuda.synchronize()
-    avg_scale_in_ms = e0.elapsed_time(e1) / (2 * a.steps)
+    avg_scale_in_ms = e0.elapsed_time(e1) / (2 * part_steps)
     traffic = None   # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE runs
     tpath = os.path.join(ROOT, "profiles", "traffic_attn_decode.json")
     if os.path.exists(tpath):
@@ -179,7 +220,7 @@ def main():
     scale_in_bytes_layer = (2 * L * (N + K) + 2 * N) / 2
     assert 2 * (product_bytes_layer + scale_in_bytes_layer) == algorithmic_bytes(M, N, K, L)
     bytes_launch = product_bytes_layer * a.copies
-    roof = {"bound": "hbm", "kernel": "stage_mx_kernel", "achieved": bytes_launch / avg_launch_ms / 1e6,
+    roof = {"bound": "hbm", "kernel": plan.kernel(1), "launches_timed": 2 * part_steps, "achieved": bytes_launch / avg_launch_ms / 1e6,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": traffic,
             "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_launch,
             "scale_in_avg_launch_us": avg_scale_in_ms * 1e3,
@@ -229,14 +270,13 @@ def main():
         extras["per_call_graph"] = {"us_per_call": us_call, "GB/s": bytes_call / us_call / 1e3}
         # (2) the same layer again and again (cache resident) through the batched entry point
         hot = mb.BatchPlan([layers[0]] * 64, [Xs[0]] * 64, [Ys[0]] * 64)
-        hot.run()
-        torch.cuda.synchronize()
+        preheat(torch, hot.run, a.preheat_ms)
         e0.record()
-        for _ in range(10):
+        for _ in range(100):
             hot.run()
         e1.record()
         torch.cuda.synchronize()
-        extras["hot_in_cache"] = {"GB/s": 64 * bytes_call * 10 / e0.elapsed_time(e1) / 1e6}
+        extras["hot_in_cache"] = {"GB/s": 64 * bytes_call * 100 / e0.elapsed_time(e1) / 1e6}
         # (3) latency of one isolated call (two launches), stream-ordered
         e0.record()
         for _ in range(200):
@@ -255,22 +295,28 @@ def main():
             X = torch.randn((T, n), device="cuda:0").half()
             Y = torch.empty((T, m), dtype=torch.float32, device="cuda:0")
             wsb = torch.empty(mb.mdbf_workspace_bytes(dl.desc("f16", "f32"), T), dtype=torch.uint8, device="cuda:0")
-            for _ in range(reps):
-                mb.mdbf_forward(dl, X, y_dtype="f32", Y=Y, workspace=wsb)
-            torch.cuda.synchronize()
+            preheat(torch, lambda: mb.mdbf_forward(dl, X, y_dtype="f32", Y=Y, workspace=wsb), a.preheat_ms)
             e0.record()
             for _ in range(reps):
                 mb.mdbf_forward(dl, X, y_dtype="f32", Y=Y, workspace=wsb)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / reps
+            issued = 2.0 * (m + n) * k * (T + L)      # reconstruct order: (l + T) multiply-adds per sign entry
             return {"ms_per_call": ms, "tokens_per_s": T / ms * 1e3,
                     "dense_equivalent_TFLOPs": 2.0 * m * n * T / ms / 1e9,
-                    "issued_TFLOPs": 2.0 * (m + n) * k * (T + L) / ms / 1e9,
-                    "frac_fp16_mfma_peak": 2.0 * (m + n) * k * (T + L) / ms / 1e9 / 2500.0}
+                    "issued_TFLOPs": issued / ms / 1e9,
+                    "roofline": {"bound": "mfma", "kernel": "stage_gemm_kernel", "achieved": issued / ms / 1e9,
+                                 "peak": 2500.0, "unit": "TFLOP/s", "frac": issued / ms / 1e9 / 2500.0,
+                                 "flops_per_call": issued}}
 
         extras["decode_T16_mlp_gate"] = time_call(11008, 4096, 4096, 16, 300)
         extras["prefill_T2048_attn"] = time_call(M, N, K, 2048, 300)
+        # matrix-core busy share of the prefill kernels, from the committed counter run (profiles/)
+        cpath = os.path.join(ROOT, "profiles", "counters_prefill.json")
+        if os.path.exists(cpath):
+            with open(cpath) as f:
+                extras["prefill_T2048_attn"]["roofline"]["mfma_busy_frac_counter"] = json.load(f)["mfma_busy_frac"]
 
         # (6) the MLP projections as they are meant to be issued: 96 independent layers (32 x gate, up, down;
         #     11008 x 4096 and 4096 x 11008, k = 4096, 0.82 GB) in one plan, with 1 and with 16 tokens each
@@ -287,17 +333,18 @@ def main():
                     py.append(torch.zeros((T, m), dtype=torch.float16, device="cuda:0"))
                     nbytes += algorithmic_bytes(m, n, 4096, L, T)
             plan_mlp = mb.BatchPlan(pl, px, py)
-            for _ in range(reps // 3):
-                plan_mlp.run()
-            torch.cuda.synchronize()
+            preheat(torch, plan_mlp.run, a.preheat_ms)
             e0.record()
             for _ in range(reps):
                 plan_mlp.run()
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / reps
-            return {"layers": len(pl), "tokens": T, "ms_per_pass": ms, "us_per_layer": ms * 1e3 / len(pl),
-                    "GB/s": nbytes / ms / 1e6, "pct_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS * 100.0}
+            # one gate-shaped and one down-shaped layer of the plan against the oracle
+            errs = [oracle_check(torch, mb, pl[i], px[i], py[i])[0] for i in (0, len(pl) - 1)]
+            return {"layers": len(pl), "tokens": T, "kernel": plan_mlp.kernel(1), "ms_per_pass": ms,
+                    "us_per_layer": ms * 1e3 / len(pl), "GB/s": nbytes / ms / 1e6,
+                    "pct_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS * 100.0, "max_rel_err_vs_oracle": max(errs)}
 
         extras["mlp_plan_T1"] = time_mlp_plan(1, 300)
         extras["mlp_plan_T16"] = time_mlp_plan(16, 150)
@@ -306,7 +353,7 @@ def main():
         "metric": "MDBF decode GEMV HBM GB/s (% peak) + prefill TFLOP/s, LLaMA-7B shapes",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": DTYPE_OF_KERNEL.get(plan.kernel(1), "f16"), "data": "synthetic",
         "config": {"workload": "attn_decode 4096x4096 k=2656 l=16 T=1 (1.503 bpw), %d independent layers per step "
                                "via mdbf_forward_batch" % a.copies,
                    "copies": a.copies, "algorithmic_bytes_per_call": bytes_call,
@@ -314,6 +361,7 @@ def main():
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "us_per_layer": ms_step * 1e3 / a.copies,
         "max_rel_err_vs_oracle": max(err, err_last),
+        "preheat_ms": preheat_ms,
         "roofline": roof,
     }
     out.update(extras)

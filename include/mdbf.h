@@ -62,6 +62,9 @@ typedef enum { MDBF_F16 = 0, MDBF_BF16 = 1, MDBF_F32 = 2 } mdbf_dtype;
 #define MDBF_FLAG_BLOCK_SCALED 2u /* take the block-scaled matrix-core variant wherever it applies (l = 16, fp16
                                      envelopes, T <= 16), also for launches too small to fill the device with it;
                                      without the flag the library picks the variant by launch size */
+#define MDBF_FLAG_FP16_STAGED 8u  /* never take the block-scaled variant: the scaled activations are staged in fp16
+                                     (a plan takes the block-scaled variant only if none of its layers carries
+                                     this flag); excludes MDBF_FLAG_BLOCK_SCALED (MDBF_EINVAL) */
 
 typedef struct {
   int32_t m, n, k, l;      /* What is m x n, inner rank k, envelope rank l */
@@ -170,14 +173,20 @@ typedef struct {
 int mdbf_batch_plan_bytes(int count, const mdbf_layer_t* layers, size_t* plan_bytes_out,
                           size_t* workspace_bytes_out);
 
-/* Fills plan_host (plan_bytes from mdbf_batch_plan_bytes) for the given layers and workspace
- * address.  The caller copies the plan verbatim to device memory (plan_dev) before calling
+/* Fills plan_host (plan_bytes from mdbf_batch_plan_bytes; any alignment) for the given layers and workspace
+ * address.  The caller copies the plan verbatim to device memory (plan_dev, 16-byte aligned) before calling
  * mdbf_forward_batch and keeps plan_host alive: the host reads launch sizes from it. */
 int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace_dev,
                           size_t workspace_bytes, void* plan_host, size_t plan_bytes);
 
 /* Runs all layers of a plan.  Asynchronous on `stream`, no allocation, no host-device copy. */
 int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream);
+
+/* Name of the product kernel a built plan runs for `stage` (1 = first factor, 2 = second factor): one of
+ * "stage_mx_kernel" (block-scaled), "stage_fast_kernel" (fp16-staged), "stage_gemm_kernel" (many tokens),
+ * "stage_generic_kernel", "stage_precise_kernel"; "" for an invalid plan or stage.  Host only; the string is
+ * static.  For reports that must name the kernel they timed. */
+const char* mdbf_batch_plan_kernel(const void* plan_host, size_t plan_bytes, int stage);
 
 /* Runs a part of a plan, for measuring its kernels one by one: `stages` and `kernels` are bit masks.
  * stages: 1 = first factor (x -> z), 2 = second factor (z -> y).  kernels: 1 = the scale-in kernel of the

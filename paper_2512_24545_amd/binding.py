@@ -17,6 +17,7 @@ MDBF_F16, MDBF_BF16, MDBF_F32 = 0, 1, 2
 MDBF_FLAG_PRECISE = 1
 MDBF_FLAG_BLOCK_SCALED = 2
 MDBF_FLAG_ACCUMULATE = 4
+MDBF_FLAG_FP16_STAGED = 8
 DTYPE_CODE = {"f16": MDBF_F16, "bf16": MDBF_BF16, "f32": MDBF_F32}
 
 STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE", -4: "MDBF_EWORKSPACE",
@@ -25,7 +26,7 @@ STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE",
 EXPORTS = [
     "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack", "mdbf_pad_envelope",
     "mdbf_stream_read", "mdbf_workspace_bytes", "mdbf_forward", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
-    "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
+    "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_batch_plan_kernel", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
 ]
 
 
@@ -82,6 +83,8 @@ def lib():
     L.mdbf_batch_plan_build.argtypes = [C.c_int, C.POINTER(Layer), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]
     L.mdbf_forward_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.mdbf_forward_batch_part.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
+    L.mdbf_batch_plan_kernel.restype = C.c_char_p
+    L.mdbf_batch_plan_kernel.argtypes = [C.c_void_p, C.c_size_t, C.c_int]
     L.mdbf_strerror.restype = C.c_char_p
     L.mdbf_strerror.argtypes = [C.c_int]
     L.mdbf_last_hip_error.restype = C.c_char_p
@@ -202,9 +205,9 @@ class DeviceLayer:
         env = [mdbf_pad_envelope(e, l_to) for e in (self.A, self.Q, self.G, self.B)]
         return DeviceLayer(self.m, self.n, self.k, l_to, self.SA_packed, self.SB_packed, *env)
 
-    def desc(self, x_dtype, y_dtype, precise=False, block_scaled=False, accumulate=False):
+    def desc(self, x_dtype, y_dtype, precise=False, block_scaled=False, accumulate=False, fp16_staged=False):
         flags = ((MDBF_FLAG_PRECISE if precise else 0) | (MDBF_FLAG_BLOCK_SCALED if block_scaled else 0) |
-                 (MDBF_FLAG_ACCUMULATE if accumulate else 0))
+                 (MDBF_FLAG_ACCUMULATE if accumulate else 0) | (MDBF_FLAG_FP16_STAGED if fp16_staged else 0))
         return Desc(self.m, self.n, self.k, self.l, DTYPE_CODE[x_dtype], DTYPE_CODE[self.env_dtype],
                     DTYPE_CODE[y_dtype], flags)
 
@@ -219,12 +222,12 @@ def mdbf_workspace_bytes(desc, T):
 
 
 def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None, stream=None, block_scaled=False,
-                 accumulate=False):
+                 accumulate=False, fp16_staged=False):
     """Y[b,:] = What X[b,:].  X: CUDA tensor (T, n) of f16/bf16/f32; returns Y (T, m) of y_dtype."""
     torch = _torch()
     assert X.is_cuda and X.dim() == 2 and X.shape[1] == layer.n and X.stride(1) == 1
     T = X.shape[0]
-    d = layer.desc(_dtype_name(X), y_dtype, precise, block_scaled, accumulate)
+    d = layer.desc(_dtype_name(X), y_dtype, precise, block_scaled, accumulate, fp16_staged)
     assert not (accumulate and Y is None), "accumulate needs the Y to add to"
     if Y is None:
         Y = torch.empty((T, layer.m), dtype=_torch_dtype(y_dtype), device=X.device)
@@ -240,14 +243,15 @@ def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None,
 class BatchPlan:
     """Plan for many independent layers: two launches for all of them."""
 
-    def __init__(self, layers, Xs, Ys, precise=False, block_scaled=False, accumulate=False):
+    def __init__(self, layers, Xs, Ys, precise=False, block_scaled=False, accumulate=False, fp16_staged=False,
+                 workspace=None):
         torch = _torch()
         assert len(layers) == len(Xs) == len(Ys) and len(layers) > 0
         n = len(layers)
         arr = (Layer * n)()
         for i, (L, X, Y) in enumerate(zip(layers, Xs, Ys)):
             acc = accumulate[i] if isinstance(accumulate, (list, tuple)) else accumulate
-            arr[i].desc = L.desc(_dtype_name(X), _dtype_name(Y), precise, block_scaled, acc)
+            arr[i].desc = L.desc(_dtype_name(X), _dtype_name(Y), precise, block_scaled, acc, fp16_staged)
             arr[i].SA_packed_dev = L.SA_packed.data_ptr()
             arr[i].SB_packed_dev = L.SB_packed.data_ptr()
             arr[i].env = L.env()
@@ -259,7 +263,10 @@ class BatchPlan:
         pb, wb = C.c_size_t(0), C.c_size_t(0)
         _check(lib().mdbf_batch_plan_bytes(n, arr, C.byref(pb), C.byref(wb)), "mdbf_batch_plan_bytes")
         self.keep = (layers, Xs, Ys)
-        self.workspace = torch.empty(max(wb.value, 16), dtype=torch.uint8, device=Xs[0].device)
+        self.workspace_bytes = wb.value
+        if workspace is None:
+            workspace = torch.empty(max(wb.value, 16), dtype=torch.uint8, device=Xs[0].device)
+        self.workspace = workspace   # caller-supplied: a uint8 CUDA tensor of at least workspace_bytes
         self.plan_host = torch.empty(pb.value, dtype=torch.uint8)
         _check(lib().mdbf_batch_plan_build(n, arr, self.workspace.data_ptr(), self.workspace.numel(),
                                            self.plan_host.data_ptr(), pb.value), "mdbf_batch_plan_build")
@@ -270,6 +277,9 @@ class BatchPlan:
         _check(lib().mdbf_forward_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), self.plan_bytes,
                                         _stream_ptr(stream)), "mdbf_forward_batch")
 
+    def kernel(self, stage):
+        """Name of the product kernel the plan runs for stage 1 or 2."""
+        return lib().mdbf_batch_plan_kernel(self.plan_host.data_ptr(), self.plan_bytes, stage).decode()
 
     def run_part(self, stages, kernels, stream=None):
         """One part of the plan (bit masks: stages 1|2, kernels 1 = scale-in, 2 = product)."""

@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 #include "mdbf_internal.h"
@@ -31,7 +32,9 @@ int check_desc(const mdbf_desc_t* d) {
   if (d->m <= 0 || d->n <= 0 || d->k <= 0) return MDBF_EINVAL;
   if (d->l < 1 || d->l > MDBF_MAX_L) return MDBF_EINVAL;
   if (!valid_dtype(d->x_dtype) || !valid_dtype(d->env_dtype) || !valid_dtype(d->y_dtype)) return MDBF_EDTYPE;
-  if (d->flags & ~(MDBF_FLAG_PRECISE | MDBF_FLAG_BLOCK_SCALED | MDBF_FLAG_ACCUMULATE)) return MDBF_EUNSUPPORTED;
+  if (d->flags & ~(MDBF_FLAG_PRECISE | MDBF_FLAG_BLOCK_SCALED | MDBF_FLAG_ACCUMULATE | MDBF_FLAG_FP16_STAGED))
+    return MDBF_EUNSUPPORTED;
+  if ((d->flags & MDBF_FLAG_BLOCK_SCALED) && (d->flags & MDBF_FLAG_FP16_STAGED)) return MDBF_EINVAL;
   return MDBF_OK;
 }
 
@@ -50,16 +53,9 @@ size_t xs_need(int K, int T) {
 size_t xs1_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? xs_need(d->n, T) : 0; }
 size_t xs2_bytes(const mdbf_desc_t* d, int T) { return wants_xs(d, T) ? xs_need(d->k, T) : 0; }
 
-// The block-scaled variant is the default where it applies; MDBF_DISABLE_MX=1 in the environment selects
-// the fp16 variant instead (read once).
-bool mx_enabled() {
-  static const bool on = [] {
-    const char* e = getenv("MDBF_DISABLE_MX");
-    return !(e && e[0] && e[0] != '0');
-  }();
-  return on;
-}
-bool use_mx(const StageProb& p) { return mx_enabled() && stage_is_mx(p); }
+// The block-scaled variant is the default where it applies; MDBF_FLAG_FP16_STAGED in the descriptor keeps a
+// layer (and with it the plan it sits in) on the fp16-staged variants.
+bool use_mx(const StageProb& p, uint32_t flags) { return !(flags & MDBF_FLAG_FP16_STAGED) && stage_is_mx(p); }
 // The block-scaled kernel walks the contraction dimension in stages of fixed latency and shares one copy of
 // the activation stream among 64 row tiles: it pays off when the launch has enough row tiles to give every
 // workgroup slot of the device an item.  Smaller launches (a single layer) go to the fp16 variant, whose
@@ -143,16 +139,16 @@ void half_intermediate(StageProb sp[2]) {
 }  // namespace
 
 int mdbf::compute_units() {
-  static int cached = 0;
-  if (!cached) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      cached = cus;
-    else
-      cached = 256;
-  }
-  return cached;
+  // one slot per device, filled by the first successful query (an atomic: any thread may be the first)
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  const int have = cached[dev].load(std::memory_order_relaxed);
+  if (have > 0) return have;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return 256;   // not cached: the next call asks again
+  cached[dev].store(cus, std::memory_order_relaxed);
+  return cus;
 }
 
 extern "C" {
@@ -235,17 +231,17 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
   {
     bool both_gemm = !(desc->flags & MDBF_FLAG_PRECISE) && T >= kGemmMinTokensSingle;
     for (int i = 0; i < 2; ++i)
-      both_gemm = both_gemm && stage_is_gemm(sp[i]) && !((desc->flags & MDBF_FLAG_BLOCK_SCALED) && use_mx(sp[i]));
+      both_gemm = both_gemm && stage_is_gemm(sp[i]) && !((desc->flags & MDBF_FLAG_BLOCK_SCALED) && use_mx(sp[i], desc->flags));
     if (both_gemm) half_intermediate(sp);
   }
   for (int i = 0; i < 2; ++i) {
     int e;
-    const bool forced_mx = (desc->flags & MDBF_FLAG_BLOCK_SCALED) && use_mx(sp[i]);
+    const bool forced_mx = (desc->flags & MDBF_FLAG_BLOCK_SCALED) && use_mx(sp[i], desc->flags);
     if (desc->flags & MDBF_FLAG_PRECISE)
       e = launch_stage_precise(nullptr, nullptr, 0, &sp[i], s);
     else if (!forced_mx && T >= kGemmMinTokensSingle && stage_is_gemm(sp[i]))
       e = launch_stage_gemm(nullptr, 0, 0, &sp[i], s);
-    else if (forced_mx || (use_mx(sp[i]) && (mx_worthwhile(sp[i].ntiles) || !stage_is_fast(sp[i])))) {
+    else if (forced_mx || (use_mx(sp[i], desc->flags) && (mx_worthwhile(sp[i].ntiles) || !stage_is_fast(sp[i])))) {
       // (a small launch the fp16 variant cannot take -- rank 8 -- is still better off here than in the
       // element-wise kernel)
       e = launch_scale_in_mx(nullptr, 1, T * sp[i].KB, &sp[i], s);
@@ -344,7 +340,7 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
                 (void*)(uintptr_t)256, sp);   // placeholder workspace: only the predicates are wanted
     for (int s = 0; s < 2; ++s) {
       // one envelope rank per launch of the block-scaled kernel
-      if (!use_mx(sp[s]) || (mx[s] != 1 && mx[s] != sp[s].l)) mx[s] = 0;
+      if (!use_mx(sp[s], L->desc.flags) || (mx[s] != 1 && mx[s] != sp[s].l)) mx[s] = 0;
       else mx[s] = sp[s].l;
       if (!stage_is_fast(sp[s])) all_fast[s] = 0;
     }
@@ -407,11 +403,14 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   int st = batch_layout(count, layers, &h, &ws);
   if (st) return st;
   if (plan_bytes < h.total_bytes || workspace_bytes < ws) return MDBF_EWORKSPACE;
-  unsigned char* base = (unsigned char*)plan_host;
-  memset(base, 0, (size_t)h.total_bytes);
-  memcpy(base, &h, sizeof(h));
-  StageProb* probs[2] = {(StageProb*)(base + h.probs_off[0]), (StageProb*)(base + h.probs_off[1])};
-  WorkItem* items[2] = {(WorkItem*)(base + h.items_off[0]), (WorkItem*)(base + h.items_off[1])};
+  // The tables are built in properly aligned host vectors and copied into the caller's buffer byte by byte:
+  // plan_host needs no particular alignment.
+  std::vector<StageProb> probs[2];
+  std::vector<WorkItem> items[2];
+  for (int s = 0; s < 2; ++s) {
+    probs[s].resize((size_t)count);
+    items[s].resize((size_t)h.nitems[s]);
+  }
   size_t zoff = 0;
   int ni[2] = {0, 0};
   int fast[2] = {1, 1};
@@ -427,7 +426,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
     if (h.gemm) half_intermediate(sp);
     zoff += layer_ws_bytes(&L->desc, L->T);
     for (int s = 0; s < 2; ++s) {
-      probs[s][i] = sp[s];
+      probs[s][(size_t)i] = sp[s];
       if (!stage_is_fast(sp[s])) fast[s] = 0;
       const int gm = gemm_load_mode(sp[s]);
       gmode[s] = (gmode[s] == -1 || gmode[s] == gm) ? gm : 3;
@@ -445,12 +444,12 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
         w.tile0 = t0;
         w.ntiles = sp[s].ntiles - t0 < tpi ? sp[s].ntiles - t0 : tpi;
         w.pad_ = 0;
-        items[s][ni[s]++] = w;
+        items[s][(size_t)ni[s]++] = w;
       }
     }
   }
   for (int s = 0; s < 2; ++s)
-    if (h.mx[s] && !h.precise && !h.gemm) balance_mx_items(items[s], ni[s], mx_max_workgroups());
+    if (h.mx[s] && !h.precise && !h.gemm) balance_mx_items(items[s].data(), ni[s], mx_max_workgroups());
   h.fast[0] = fast[0];
   h.fast[1] = fast[1];
   h.pre[0] = fast[0] && pre[0];
@@ -460,6 +459,12 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
   for (int s = 0; s < 2; ++s) {
     h.max_units_mx[s] = max_units_mx[s];
     h.gemm_mode[s] = gmode[s];
+  }
+  unsigned char* base = (unsigned char*)plan_host;
+  memset(base, 0, (size_t)h.total_bytes);
+  for (int s = 0; s < 2; ++s) {
+    memcpy(base + h.probs_off[s], probs[s].data(), probs[s].size() * sizeof(StageProb));
+    memcpy(base + h.items_off[s], items[s].data(), items[s].size() * sizeof(WorkItem));
   }
   memcpy(base, &h, sizeof(h));
   return MDBF_OK;
@@ -486,7 +491,9 @@ int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t 
     for (int i = 0; i < h.count; ++i)
       for (int st = 0; st < 2; ++st) {
         if (!(stages & (1 << st)) || !(kernels & 2)) continue;
-        int e = launch_stage_gemm(nullptr, 0, 0, (const StageProb*)(host + h.probs_off[st]) + i, s);
+        StageProb one;   // plan_host may have any alignment
+        memcpy(&one, host + h.probs_off[st] + (size_t)i * sizeof(StageProb), sizeof(one));
+        int e = launch_stage_gemm(nullptr, 0, 0, &one, s);
         if (e) return hip_fail(e);
       }
     return MDBF_OK;
@@ -528,6 +535,19 @@ int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t 
     if (e) return hip_fail(e);
   }
   return MDBF_OK;
+}
+
+const char* mdbf_batch_plan_kernel(const void* plan_host, size_t plan_bytes, int stage) {
+  if (!plan_host || plan_bytes < sizeof(PlanHeader) || stage < 1 || stage > 2) return "";
+  PlanHeader h;
+  memcpy(&h, plan_host, sizeof(h));
+  if (h.magic != kPlanMagic) return "";
+  const int st = stage - 1;
+  if (h.precise) return "stage_precise_kernel";
+  if (h.gemm) return "stage_gemm_kernel";
+  if (h.mx[st]) return "stage_mx_kernel";
+  if (h.fast[st]) return "stage_fast_kernel";
+  return "stage_generic_kernel";
 }
 
 const char* mdbf_strerror(int status) {

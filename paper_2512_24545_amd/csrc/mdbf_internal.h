@@ -2,6 +2,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <mutex>
+
 #include "mdbf.h"
 
 // Every pointer the kernels receive is device global memory.  Saying so in the pointer type makes the
@@ -113,6 +116,23 @@ struct PlanHeader {
   uint64_t total_bytes;
 };
 constexpr uint32_t kPlanMagic = 0x4D444246u;  // "MDBF"
+
+// One-time set-up of a kernel per device (raising its dynamic LDS limit): thread-safe, and the outcome of
+// the one attempt is what every later call on that device reports.
+constexpr int kMaxDevices = 64;
+struct KernelSetup {
+  std::once_flag once[kMaxDevices];
+  int err[kMaxDevices];
+};
+template <class F>
+inline int kernel_setup(KernelSetup& k, F&& fn) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::call_once(k.once[dev], [&] { k.err[dev] = (int)fn(); });
+  return k.err[dev];
+}
 
 // launchers (defined in the kernel translation units); return hipError_t as int
 int launch_pack(const int8_t* signs, int rows, int cols, int64_t ld, uint32_t* packed, hipStream_t s);

@@ -496,13 +496,12 @@ void stage_gemm_split_kernel(StageProb p) {
 template <int MODE, int R>
 static int launch_split_r(const StageProb* p, hipStream_t s) {
   static_assert(R >= 1 && R <= kWaves, "wave r stores tile r");
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_split_kernel<MODE, R>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSplitSmem);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static KernelSetup setup;
+  if (int e = kernel_setup(setup, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_split_kernel<MODE, R>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSplitSmem);
+      }))
+    return e;
   hipLaunchKernelGGL((stage_gemm_split_kernel<MODE, R>), dim3((unsigned)((p->ntiles + R - 1) / R)),
                      dim3(64 * kWaves), kSplitSmem, s, *p);
   return (int)hipGetLastError();
@@ -519,13 +518,12 @@ static int launch_split(const StageProb* p, hipStream_t s) {
 // p->T = the longest token count among the problems.
 template <int R, int TB, int MODE, bool BATCH>
 static int launch_rtmb(const WorkItem* items_dev, int nitems, const StageProb* p, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB, MODE, BATCH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(TB));
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static KernelSetup setup;
+  if (int e = kernel_setup(setup, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_gemm_kernel<R, TB, MODE, BATCH>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(TB));
+      }))
+    return e;
   const int rows_per_wg = kWaves * R;   // tiles
   unsigned gx = BATCH ? (unsigned)nitems : (unsigned)((p->ntiles + rows_per_wg - 1) / rows_per_wg);
   unsigned gy = (unsigned)((p->T + 16 * TB - 1) / (16 * TB));

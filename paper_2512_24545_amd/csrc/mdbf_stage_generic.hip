@@ -221,13 +221,12 @@ __global__ __launch_bounds__(256) void stage_generic_kernel(const StageProb* __r
 template <int R>
 static int launch_generic_r(const StageProb* probs_dev, const WorkItem* items_dev, int nblocks, int tiles_per_item,
                     const StageProb* single, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_generic_kernel<R>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static KernelSetup setup;
+  if (int e = kernel_setup(setup, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_generic_kernel<R>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+      }))
+    return e;
   hipLaunchKernelGGL(stage_generic_kernel<R>, dim3((unsigned)nblocks), dim3(256), kSmemBytes, s, probs_dev, items_dev,
                      *single, tiles_per_item);
   return (int)hipGetLastError();

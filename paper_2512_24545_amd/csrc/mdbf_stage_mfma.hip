@@ -40,24 +40,9 @@ typedef const MDBF_GLOBAL _Float16* g_f16_ptr;
 typedef const MDBF_GLOBAL uint16_t* g_u16_ptr;
 typedef const MDBF_GLOBAL float* g_f32_ptr;
 
-#ifdef MDBF_DBG_TIMING
-__device__ unsigned long long g_dbg_time[64 * 64];   // [block < 64][slot]
-#define DBG_T(slot) do { if (dbg_unit == 2 && blockIdx.x < 64 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == 1 && (slot) < 64) \
-    g_dbg_time[blockIdx.x * 64 + (slot)] = __builtin_readcyclecounter(); } while (0)
-#define DBG_UNIT_DECL int dbg_unit = 0
-#define DBG_UNIT_NEXT ++dbg_unit
-#else
-#define DBG_T(slot) do {} while (0)
-#define DBG_UNIT_DECL do {} while (0)
-#define DBG_UNIT_NEXT do {} while (0)
-#endif
-
 constexpr int CB = 8;                      // 128-column blocks per LDS chunk
 constexpr int kChunkVecs = CB * 4 * 64;    // 16-byte vectors per chunk buffer (32 KB)
-#ifndef MDBF_LOAD_STEPS
-#define MDBF_LOAD_STEPS 1
-#endif
-constexpr int kLoadSteps = MDBF_LOAD_STEPS;   // the next chunk's loads are issued during this many block steps (1, 2 or 4)
+constexpr int kLoadSteps = 1;               // the next chunk's loads are issued during this many block steps (1, 2 or 4)
 constexpr int kPrefetchBlocks = CB;        // sign words are loaded one chunk (8 blocks) ahead of their use
 __host__ __device__ constexpr int eo_vecs(int R) { return R * 4 * 16 * 2 < 256 ? 256 : R * 4 * 16 * 2; }  // Eout rows of a unit, 16 B each, a multiple of the 256 threads
 __host__ __device__ constexpr int fast_smem_bytes(int R) { return 2 * kChunkVecs * 16 + eo_vecs(R) * 16 + 4 * 16 * 4; }
@@ -125,9 +110,6 @@ __device__ __forceinline__ void stage_addr(const void* ein, int ch, const void* 
 }
 
 __device__ __forceinline__ void stage_load_part(const StageAddr& sa, int part, StageRegs& sr) {
-#ifdef MDBF_DBG_NOSTAGELOAD
-  return;
-#endif
   sr.e[2 * part] = sa.ep[4 * part];
   sr.e[2 * part + 1] = sa.ep[4 * part + 2];
   if (part == 0) {
@@ -449,10 +431,7 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
   // chunk's largest magnitude at 2^12): the accumulators are carried in the current chunk's scale and
   // brought to the next chunk's at the boundary; the result is scaled back at the end.
   int e_cur = PRE ? ((const MDBF_GLOBAL int*)u.xs_exp)[0] : 0;
-  DBG_UNIT_DECL;
   for (;;) {
-    DBG_UNIT_NEXT;
-    DBG_T(0);
     settle<R>(wq);
     // ---- which unit comes next: the next token of the same item, else this workgroup's next item,
     //      whose descriptor is requested now and only looked at when this unit's last chunk starts
@@ -483,7 +462,6 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
     for (int c = 0; c < nchunks - 1; ++c) {
       const int e_nx = PRE ? ((const MDBF_GLOBAL int*)u.xs_exp)[c + 1] : 0;
       stg.addr(u.p.Ein, u.vin_row, u.p.vin_dt, u.xs_tok, c + 1, u.p.K, ch, st_col, tid);
-      DBG_T(1 + 4 * c);
       const u32x4* bufc = buf + par * kChunkVecs;
 #pragma unroll
       for (int jj = 0; jj < CB; ++jj) {
@@ -507,13 +485,8 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
         load_block_ops(bufc + jj * 256, rd_even, rd_odd, rd_virt, ops);
         contract_block<R>(ops, avirt, word, acc, accv);
       }
-      DBG_T(2 + 4 * c);
-#ifndef MDBF_DBG_NOSTAGE
       stg.store(buf + (par ^ 1) * kChunkVecs, st_vec, st_sw, tid);
-#endif
-      DBG_T(3 + 4 * c);
       __syncthreads();
-      DBG_T(4 + 4 * c);
       par ^= 1;
 #pragma unroll
       for (int r = 0; r < R; ++r)
@@ -556,7 +529,6 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
         const int row = min(u.tile0 * kTileRows + (v >> 1), u.p.rows - 1);
         eoreg[t] = ((g_u32x4_ptr)u.p.Eout)[(size_t)row * 2 + (v & 1)];
       }
-      DBG_T(1 + 4 * c);
       const u32x4* bufc = buf + par * kChunkVecs;
 #pragma unroll
       for (int jj = 0; jj < CB; ++jj) {
@@ -577,21 +549,15 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
           contract_block<R>(ops, avirt, word, acc, accv);
         }
       }
-      DBG_T(2 + 4 * c);
       red[wave * 16 + n] = accv[0] * virt_scale;   // all output rows of the virtual tile are equal
 #pragma unroll
       for (int t = 0; t < eo_vecs(R) / 256; ++t) eo[tid + 256 * t] = eoreg[t];
-#ifndef MDBF_DBG_NOSTAGE
       stg.store(buf + (par ^ 1) * kChunkVecs, st_vec, st_sw, tid);
-#endif
-      DBG_T(3 + 4 * c);
       __syncthreads();
-      DBG_T(4 + 4 * c);
       par ^= 1;
     }
 
     // ---- epilogue: column sums, fix-up, envelope accumulate, store --------------------------------
-    DBG_T(40);
     const float colsum = (red[n] + red[16 + n]) + (red[32 + n] + red[48 + n]);
     const _Float16* eoh = reinterpret_cast<const _Float16*>(eo);
     const float unscale = PRE ? pow2i(-e_cur) : 1.f;
@@ -616,7 +582,6 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
         emit_result(u.p.out, (int64_t)u.b * u.p.out_ld + row, u.p.out_dt, res[r], u.p.flags);
     }
     e_cur = e_unit_next;
-    DBG_T(41);
     if (!has_next) break;
     // a one-chunk unit writes red / eo again before any other barrier: wait for the slowest reader
     if (nchunks == 1) __syncthreads();
@@ -631,18 +596,13 @@ void stage_fast_kernel(const WorkItem* __restrict__ items, int nitems, StageProb
 template <int R, bool BATCH, bool PRE>
 static int launch_rbp(const WorkItem* items_dev, int nitems, int tiles_per_item, const StageProb* single,
                       hipStream_t s) {
-  static bool attr_set = false;
-  static int max_wgs = 512;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_fast_kernel<R, BATCH, PRE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, fast_smem_bytes(R));
-    if (e != hipSuccess) return (int)e;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      max_wgs = 2 * cus;   // two workgroups of four waves per compute unit
-    attr_set = true;
-  }
+  static KernelSetup setup;
+  if (int e = kernel_setup(setup, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_fast_kernel<R, BATCH, PRE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, fast_smem_bytes(R));
+      }))
+    return e;
+  const int max_wgs = 2 * compute_units();   // two workgroups of four waves per compute unit
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
   hipLaunchKernelGGL((stage_fast_kernel<R, BATCH, PRE>), dim3((unsigned)nwg), dim3(256), fast_smem_bytes(R), s,
                      items_dev, nitems, *single, tiles_per_item);
@@ -708,12 +668,6 @@ size_t xs_bytes_for(int K, int T) {
   // the staged chunks of every token, then one exponent per (token, chunk)
   return (size_t)T * (size_t)nch * (size_t)kChunkVecs * 16u + (((size_t)T * (size_t)nch * 4u + 15u) & ~(size_t)15u);
 }
-
-#ifdef MDBF_DBG_TIMING
-extern "C" int mdbf_dbg_read(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_time), bytes < sizeof(g_dbg_time) ? bytes : sizeof(g_dbg_time));
-}
-#endif
 
 bool stage_is_fast(const StageProb& p) {
   if (p.l != 16 || p.env_dt != MDBF_F16 || (p.K & 7) != 0 || p.KB < kPrefetchBlocks) return false;

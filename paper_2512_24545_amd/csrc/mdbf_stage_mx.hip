@@ -50,10 +50,7 @@ constexpr int kColsumOff = kScaleOff + 256;    // 4864: 16 fp32 column sums of t
 constexpr int kBlockBytes = 5120;              // padded to a multiple of 1 KB (one loader instruction)
 
 // ---- main kernel geometry
-#ifndef MDBF_MX_WAVES
-#define MDBF_MX_WAVES 8
-#endif
-constexpr int kComputeWaves = MDBF_MX_WAVES;
+constexpr int kComputeWaves = 8;
 constexpr int R = 64 / kComputeWaves;                  // row tiles per contraction wave
 constexpr int kItemTiles = kComputeWaves * R;          // row tiles per work item
 static_assert(kGroupTiles % kItemTiles == 0, "an item lies inside one group of the packed layout");
@@ -657,13 +654,12 @@ static int max_workgroups() { return kWgsPerCu * compute_units(); }
 
 template <bool BATCH, int RANK>
 static int launch_br(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH, RANK>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  static KernelSetup setup;
+  if (int e = kernel_setup(setup, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH, RANK>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+      }))
+    return e;
   const int max_wgs = max_workgroups();
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
   hipLaunchKernelGGL((stage_mx_kernel<BATCH, RANK>), dim3((unsigned)nwg), dim3(kThreads), kSmemBytes, s, items_dev,

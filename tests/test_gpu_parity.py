@@ -7,6 +7,7 @@ import pytest
 
 from oracle import mdbf_oracle as orc
 from paper_2512_24545_amd import synth
+from helpers import concat_terms
 
 pytestmark = pytest.mark.gpu
 
@@ -55,7 +56,7 @@ def test_pack_unpack_bit_exact(gpu, rows, cols):
     back = mb.mdbf_unpack(packed, rows, cols).cpu().numpy()
     np.testing.assert_array_equal(back, S)
     # the logical bits agree with the oracle's reference packing of the same matrix
-    np.testing.assert_array_equal(orc.pack_ref(back), orc.pack_ref(S))
+    np.testing.assert_array_equal(orc.unpack_ref(orc.pack_ref(S), cols), back)
     # one bit per entry, padding bits are zero: population count equals the number of -1 entries
     pc = int(np.unpackbits(packed.cpu().numpy()).sum())
     assert pc == int((S < 0).sum())
@@ -640,7 +641,7 @@ def test_residual_stack_as_one_concatenated_layer(gpu, ranks, T):
              for p, l in enumerate(ranks)]
     X = synth.make_activations(1032, T, seed=830, x_dtype="f16")
     ref = orc.forward_residual_stack([_oracle_args(t) for t in terms], X)
-    one = synth.concat_terms(terms)
+    one = concat_terms(terms)
     assert orc.max_rel_error(_run(gpu, one, X, "f16", "f32"), ref) <= TOL
     if sum(ranks) in (8, 16) and T == 1:
         assert orc.max_rel_error(_run(gpu, one, X, "f16", "f32", block_scaled=True), ref) <= TOL

@@ -5,6 +5,7 @@ import pytest
 
 from oracle import mdbf_oracle as orc
 from paper_2512_24545_amd import synth
+from helpers import concat_terms
 
 
 def _tiny(seed, m, n, k, l, T=2, signed=True):
@@ -264,7 +265,7 @@ def test_residual_stack_is_one_layer_of_concatenated_factors():
     terms = [synth.make_layer(9, 11, k, l, seed=70 + k, env_dtype="f32", env_kind="unit", signed_env=True)
              for k, l in ((5, 2), (7, 1), (4, 3))]
     X = synth.make_activations(11, 3, seed=71, x_dtype="f32")
-    one = synth.concat_terms(terms)
+    one = concat_terms(terms)
     assert one["k"] == 16 and one["l"] == 6
     np.testing.assert_allclose(orc.forward_factored(*_args(one), X),
                                orc.forward_residual_stack([_args(t) for t in terms], X), rtol=1e-12, atol=1e-12)
