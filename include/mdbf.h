@@ -154,6 +154,25 @@ int mdbf_forward(const mdbf_desc_t* desc,
                  void* Y_dev, int64_t ldy, int T,
                  void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/* mdbf_forward without a workspace argument, for callers that cannot allocate device memory at all (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) and therefore have no
+ * workspace to pass.  Same arguments, kernels, arithmetic and results as mdbf_forward; the scratch memory
+ * (the inner vector z and the scaled activations) lives in a static device array of
+ * MDBF_STATIC_SCRATCH_BYTES inside the library, which every GPU the library runs on holds until the process
+ * ends.  The call allocates and frees nothing.  A request whose mdbf_workspace_bytes() exceeds
+ * MDBF_STATIC_SCRATCH_BYTES returns MDBF_EWORKSPACE (checked on the host, before any HIP call): every layer
+ * shape up to 11008 x 11008 with k <= 8192 fits with T <= 16; the 2048-token prefill does not.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams,
+ * or a captured graph replayed while another call runs) race on it; calls on one stream are ordered and safe.
+ * The array keeps the last call's contents; no kernel depends on them.  The first call on a device looks up
+ * the array's address (hipGetSymbolAddress): make it outside stream capture. */
+#define MDBF_STATIC_SCRATCH_BYTES (16u << 20)
+int mdbf_forward_static(const mdbf_desc_t* desc,
+                        const void* SA_packed_dev, const void* SB_packed_dev,
+                        const mdbf_env_t* env,
+                        const void* X_dev, int64_t ldx,
+                        void* Y_dev, int64_t ldy, int T, void* stream);
+
 /* ---- many independent layers in one pair of launches -----------------------------------
  * One entry per layer; the same meaning as the arguments of mdbf_forward.  Serves sibling
  * projections and whole stacks of independent products with two kernel launches in total. */

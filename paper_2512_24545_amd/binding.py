@@ -25,7 +25,7 @@ STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE",
 
 EXPORTS = [
     "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack", "mdbf_pad_envelope",
-    "mdbf_stream_read", "mdbf_workspace_bytes", "mdbf_forward", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
+    "mdbf_stream_read", "mdbf_workspace_bytes", "mdbf_forward", "mdbf_forward_static", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
     "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_batch_plan_kernel", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
 ]
 
@@ -79,6 +79,8 @@ def lib():
     L.mdbf_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int, C.POINTER(C.c_size_t)]
     L.mdbf_forward.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.POINTER(Env), C.c_void_p, C.c_int64,
                                C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.mdbf_forward_static.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.POINTER(Env), C.c_void_p, C.c_int64,
+                                      C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
     L.mdbf_batch_plan_bytes.argtypes = [C.c_int, C.POINTER(Layer), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     L.mdbf_batch_plan_build.argtypes = [C.c_int, C.POINTER(Layer), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]
     L.mdbf_forward_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -237,6 +239,19 @@ def mdbf_forward(layer, X, y_dtype="f32", precise=False, Y=None, workspace=None,
     _check(lib().mdbf_forward(C.byref(d), layer.SA_packed.data_ptr(), layer.SB_packed.data_ptr(), C.byref(env),
                               X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), T, workspace.data_ptr(),
                               workspace.numel(), _stream_ptr(stream)), "mdbf_forward")
+    return Y
+
+
+def mdbf_forward_static(layer, X, Y, stream=None, block_scaled=False, fp16_staged=False, precise=False):
+    """mdbf_forward on the library's static scratch array: no workspace argument, nothing allocated here
+    either (the caller passes Y)."""
+    assert X.is_cuda and X.dim() == 2 and X.shape[1] == layer.n and X.stride(1) == 1
+    assert Y.is_cuda and Y.shape == (X.shape[0], layer.m) and Y.stride(1) == 1
+    d = layer.desc(_dtype_name(X), _dtype_name(Y), precise, block_scaled, False, fp16_staged)
+    env = layer.env()
+    _check(lib().mdbf_forward_static(C.byref(d), layer.SA_packed.data_ptr(), layer.SB_packed.data_ptr(),
+                                     C.byref(env), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0),
+                                     X.shape[0], _stream_ptr(stream)), "mdbf_forward_static")
     return Y
 
 

@@ -264,6 +264,54 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
   return MDBF_OK;
 }
 
+// ---- scratch memory of mdbf_forward_static: one array per device, owned by the loaded code object.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the device address is looked up once per
+// device (with that device current) and kept.
+}  // extern "C"
+static __device__ __align__(256) unsigned char scratch[MDBF_STATIC_SCRATCH_BYTES];
+namespace {
+constexpr size_t kStaticScratchBytes = MDBF_STATIC_SCRATCH_BYTES;
+struct ScratchSlots {
+  std::once_flag once[kMaxDevices];
+  void* ptr[kMaxDevices];
+  int err[kMaxDevices];
+};
+ScratchSlots g_scratch;
+// device address of the current device's copy of `scratch`; returns a hipError_t as int
+int static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::call_once(g_scratch.once[dev], [&] {
+    void* p = nullptr;
+    hipError_t r = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    g_scratch.ptr[dev] = (r == hipSuccess) ? p : nullptr;
+    g_scratch.err[dev] = (int)r;
+  });
+  if (g_scratch.err[dev]) return g_scratch.err[dev];
+  if (!g_scratch.ptr[dev]) return (int)hipErrorInvalidSymbol;
+  *out = g_scratch.ptr[dev];
+  return 0;
+}
+}  // namespace
+extern "C" {
+
+int mdbf_forward_static(const mdbf_desc_t* desc, const void* SA_packed_dev, const void* SB_packed_dev,
+                        const mdbf_env_t* env, const void* X_dev, int64_t ldx, void* Y_dev, int64_t ldy, int T,
+                        void* stream) {
+  int st = check_layer(desc, SA_packed_dev, SB_packed_dev, env, X_dev, ldx, Y_dev, ldy, T);
+  if (st) return st;
+  if (layer_ws_bytes(desc, T) > kStaticScratchBytes) return MDBF_EWORKSPACE;
+  void* ws = nullptr;
+  int e = static_scratch(&ws);
+  if (e) return hip_fail(e);
+  // Nothing in the scratch has to start at zero: every byte a kernel of the call reads (z, the scaled
+  // activations' records) is written earlier in the same call.
+  return mdbf_forward(desc, SA_packed_dev, SB_packed_dev, env, X_dev, ldx, Y_dev, ldy, T, ws, kStaticScratchBytes,
+                      stream);
+}
+
 // Work items of a stage of the block-scaled kernel, reordered for its static schedule.  The kernel's
 // workgroups (nwg of them; groups of nwg / 8 per XCD when nwg is a multiple of 8) walk a contiguous slice
 // [lo, hi) of the table: workgroup j of the slice takes entries lo + j, lo + j + stride, ..., so the first

@@ -261,3 +261,18 @@ def test_strerror():
     assert L.mdbf_strerror(0) == b"ok"
     assert b"aligned" in L.mdbf_strerror(-2)
     assert L.mdbf_last_hip_error() == b""
+
+
+def test_static_scratch_call_checks_its_limit_on_the_host():
+    """mdbf_forward_static: the same argument checks as mdbf_forward, and a request beyond the static array's
+    16 MiB is refused before any HIP call (this host has no GPU)."""
+    d = mb.Desc(4096, 4096, 2656, 16, mb.MDBF_F16, mb.MDBF_F16, mb.MDBF_F32, 0)
+    env = mb.Env(FAKE, FAKE, FAKE, FAKE)
+    need = C.c_size_t(0)
+    assert mb.lib().mdbf_workspace_bytes(C.byref(d), 2048, C.byref(need)) == 0 and need.value > (16 << 20)
+    call = lambda desc, T, X=FAKE: mb.lib().mdbf_forward_static(C.byref(desc), FAKE, FAKE, C.byref(env), X, desc.n,
+                                                                FAKE, desc.m, T, None)
+    assert call(d, 2048) == -4                      # MDBF_EWORKSPACE
+    assert call(d, 0) == -1 and call(d, 1, None) == -1 and call(d, 1, FAKE + 4) == -2
+    bad = mb.Desc(4096, 4096, 2656, 17, mb.MDBF_F16, mb.MDBF_F16, mb.MDBF_F32, 0)
+    assert call(bad, 1) == -1
