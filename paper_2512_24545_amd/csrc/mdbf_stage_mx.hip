@@ -248,17 +248,21 @@ __device__ __forceinline__ void prep_record(const StageProb& p, int unit, int la
       a.x = slot[L][0]; a.y = slot[L][1]; a.z = slot[L][2]; a.w = slot[L][3];
       u32x2 bpart;
       bpart.x = slot[L][4]; bpart.y = slot[L][5];
-      ((MDBF_GLOBAL u32x4*)(blk + L * kLimbBytes))[lane] = a;
-      ((MDBF_GLOBAL u32x2*)(blk + L * kLimbBytes + 64 * 16))[lane] = bpart;
+      // Non-temporal stores: the records are read once, by the product launch that follows.  With plain stores
+      // the write-back of 40 to 55 MB of dirty lines runs into that launch (measured on the 336-layer
+      // workload: 257 -> 248 us per step with the hint).
+      __builtin_nontemporal_store(a, &((MDBF_GLOBAL u32x4*)(blk + L * kLimbBytes))[lane]);
+      __builtin_nontemporal_store(bpart, &((MDBF_GLOBAL u32x2*)(blk + L * kLimbBytes + 64 * 16))[lane]);
     }
   }
-  ((MDBF_GLOBAL uint32_t*)(blk + kScaleOff))[lane] = e0 | (e1 << 8) | ((uint32_t)(E + 119) << 16);
+  __builtin_nontemporal_store(e0 | (e1 << 8) | ((uint32_t)(E + 119) << 16),
+                              &((MDBF_GLOBAL uint32_t*)(blk + kScaleOff))[lane]);
   if (upper) part = 0.f;   // the column sum of a mode is stored once
 
   // ---- 3. column sums of the block
   part += __shfl_xor(part, 16);
   part += __shfl_xor(part, 32);
-  if (lane < 16) ((MDBF_GLOBAL float*)(blk + kColsumOff))[lane] = part;
+  if (lane < 16) __builtin_nontemporal_store(part, &((MDBF_GLOBAL float*)(blk + kColsumOff))[lane]);
 }
 
 template <bool RANK8>
