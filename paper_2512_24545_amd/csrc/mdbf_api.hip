@@ -321,6 +321,43 @@ int mdbf_forward_static(const mdbf_desc_t* desc, const void* SA_packed_dev, cons
 // descending cost (ties keep their order), each to the workgroup with the least cost so far among those
 // with a free entry (ties: the one with fewer entries in all, then the lowest index), so that the costliest
 // items land where fewer items go.  Slices whose items all cost the same keep their order.
+// A stage of the block-scaled kernel whose items all cost the same and do not fill a whole number of rounds
+// of the device's workgroups (1344 items on 256 workgroups: 5.25 rounds) ends with a round in which most
+// workgroups idle.  The items of that last, partial round are cut into pieces of fewer row tiles (multiples
+// of the 8 tiles a contraction wave owns), as many as give every workgroup one piece: a piece's stages are
+// shorter than a full item's (fewer waves contract, on separate SIMDs), so the last round is.  The pieces are
+// dealt to the ends of the eight per-XCD slices the kernel walks.  Returns the new number of items
+// (at most `cap`, the room of the table).
+static int split_last_round(std::vector<WorkItem>& items, int max_wgs, size_t cap) {
+  const int n = (int)items.size();
+  if (n <= max_wgs || (max_wgs & 7) != 0) return n;
+  const int r = n % max_wgs;
+  if (r == 0 || 2 * r > max_wgs) return n;
+  const long c0 = (long)items[0].p.T * ((items[0].p.KB + 1) / 2 + 1);
+  for (const WorkItem& w : items)
+    if ((long)w.p.T * ((w.p.KB + 1) / 2 + 1) != c0) return n;
+  int pieces = max_wgs / r;
+  if (pieces > 8) pieces = 8;
+  std::vector<WorkItem> full(items.begin(), items.end() - r), small;
+  for (int i = n - r; i < n; ++i) {
+    const WorkItem& w = items[(size_t)i];
+    const int per = ((w.ntiles + pieces - 1) / pieces + 7) & ~7;     // tiles per piece: whole contraction waves
+    for (int t = 0; t < w.ntiles; t += per) {
+      WorkItem q = w;
+      q.tile0 = w.tile0 + t;
+      q.ntiles = w.ntiles - t < per ? w.ntiles - t : per;
+      small.push_back(q);
+    }
+  }
+  if (full.size() + small.size() > cap) return n;
+  items.clear();
+  for (int x = 0; x < 8; ++x) {
+    items.insert(items.end(), full.begin() + (long)full.size() * x / 8, full.begin() + (long)full.size() * (x + 1) / 8);
+    items.insert(items.end(), small.begin() + (long)small.size() * x / 8, small.begin() + (long)small.size() * (x + 1) / 8);
+  }
+  return (int)items.size();
+}
+
 static void balance_mx_items(WorkItem* items, int n, int max_wgs) {
   const int nwg = n < max_wgs ? n : max_wgs;
   const int slices = (nwg & 7) == 0 ? 8 : 1;
@@ -413,7 +450,7 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
     nitems[0] += (num_tiles(layers[i].desc.k) + h->tiles_per_item[0] - 1) / h->tiles_per_item[0];
     nitems[1] += (num_tiles(layers[i].desc.m) + h->tiles_per_item[1] - 1) / h->tiles_per_item[1];
   }
-  if (nitems[0] > 65535 || nitems[1] > 65535) return MDBF_EUNSUPPORTED;
+  if (nitems[0] + mx_max_workgroups() > 65535 || nitems[1] + mx_max_workgroups() > 65535) return MDBF_EUNSUPPORTED;
   h->nitems[0] = (int)nitems[0];
   h->nitems[1] = (int)nitems[1];
   size_t off = align_up(sizeof(PlanHeader), 256);
@@ -423,7 +460,9 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
   }
   for (int s = 0; s < 2; ++s) {
     h->items_off[s] = off;
-    off = align_up(off + (size_t)nitems[s] * sizeof(WorkItem), 256);
+    // (room for the pieces the last round of a block-scaled stage may be cut into: at most one per workgroup)
+    const size_t room = (size_t)nitems[s] + (h->mx[s] ? (size_t)mx_max_workgroups() : 0u);
+    off = align_up(off + room * sizeof(WorkItem), 256);
   }
   h->total_bytes = off;
   *ws_bytes = ws;
@@ -497,7 +536,11 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
     }
   }
   for (int s = 0; s < 2; ++s)
-    if (h.mx[s] && !h.precise && !h.gemm) balance_mx_items(items[s].data(), ni[s], mx_max_workgroups());
+    if (h.mx[s] && !h.precise && !h.gemm) {
+      balance_mx_items(items[s].data(), ni[s], mx_max_workgroups());
+      ni[s] = split_last_round(items[s], mx_max_workgroups(), items[s].size() + (size_t)mx_max_workgroups());
+      h.nitems[s] = ni[s];
+    }
   h.fast[0] = fast[0];
   h.fast[1] = fast[1];
   h.pre[0] = fast[0] && pre[0];

@@ -248,12 +248,51 @@ def test_block_scaled_plan_puts_long_items_where_fewer_items_go():
         assert max(loads) == 44 and min(loads) == 34
 
 
+def _covered_once(items, shapes, s):
+    """Every row tile of every problem is in exactly one work item."""
+    seen = {}
+    for w in items:
+        for t in range(w.tile0, w.tile0 + w.ntiles):
+            assert (w.prob, t) not in seen
+            seen[(w.prob, t)] = 1
+    want = sum(((k if s == 0 else m) + 15) // 16 for (m, nn, k) in shapes)
+    assert len(seen) == want
+    for (prob, t) in seen:
+        m, nn, k = shapes[prob]
+        assert 0 <= t < ((k if s == 0 else m) + 15) // 16
+
+
 def test_block_scaled_plan_of_equal_layers_keeps_problem_order():
-    h, tables = _plan_items([(4096, 4096, 2656)] * 100)
+    """Equal layers: nothing to balance; whole rounds keep the problem order (the layers' activation records
+    are shared through one L2 by neighbouring workgroups)."""
+    shapes = [(4096, 4096, 2656)] * 256                # 768 and 1024 items: 3 and 4 whole rounds of 256 workgroups
+    h, tables = _plan_items(shapes)
     assert list(h.mx) == [16, 16]
-    for items in tables:
+    for s, items in enumerate(tables):
         got = [(w.prob, w.tile0) for w in items]
         assert got == sorted(got)
+        _covered_once(items, shapes, s)
+
+
+def test_block_scaled_plan_cuts_the_last_partial_round_into_pieces():
+    """336 equal layers: the second factor has 1344 items = 5.25 rounds of 256 workgroups.  The 64 items of the
+    last round are cut into four pieces of 16 row tiles each, one per workgroup, dealt to the ends of the eight
+    slices of the table; every row tile is still covered exactly once."""
+    shapes = [(4096, 4096, 2656)] * 336
+    h, tables = _plan_items(shapes)
+    assert list(h.mx) == [16, 16]
+    items = tables[1]
+    assert len(items) == 1280 + 256 and h.nitems[1] == len(items)
+    _covered_once(items, shapes, 1)
+    for x in range(8):
+        sl = items[192 * x: 192 * (x + 1)]
+        assert [w.ntiles for w in sl] == [64] * 160 + [16] * 32
+        full = [(w.prob, w.tile0) for w in sl[:160]]
+        assert full == sorted(full)
+        assert all(w.tile0 % 8 == 0 for w in sl)
+    # the first factor (166 row tiles: 1008 items, 3.94 rounds) has more than half a round left: not cut
+    assert len(tables[0]) == 1008
+    _covered_once(tables[0], shapes, 0)
 
 
 def test_strerror():

@@ -278,3 +278,25 @@ def test_random_shape_sweep(gpu):
             worst = max(worst, err if name != "precise" else 0.0)
             assert err <= (TOL_PRECISE if name == "precise" else TOL), (idx, name, (m, n, k, l, T, env_dtype, x_dtype), err)
     assert worst > 0.0
+
+
+def test_plan_whose_last_round_is_cut_into_pieces(gpu):
+    """160 equal layers with 128 row tiles each: 320 work items in the second factor = 1.25 rounds of 256
+    workgroups, so the 64 items of the last round are cut into 16-tile pieces (one per workgroup).  Every
+    output of every layer is compared with the oracle."""
+    torch, mb = gpu
+    layers, Xs, Ys, refs = [], [], [], []
+    for i in range(160):
+        L = synth.make_layer(2048, 384, 256, 16, seed=9100 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+        X = synth.make_activations(384, 1, seed=9300 + i, x_dtype="f16")
+        layers.append(mb.DeviceLayer.from_host(L))
+        Xs.append(_to_dev(torch, X))
+        Ys.append(torch.zeros((1, 2048), dtype=torch.float32, device="cuda:0"))
+        refs.append(orc.forward_factored(*_oracle_args(L), X))
+    plan = mb.BatchPlan(layers, Xs, Ys, block_scaled=True)
+    assert plan.kernel(2) == "stage_mx_kernel"
+    for _ in range(2):
+        plan.run()
+    torch.cuda.synchronize()
+    for Yb, ref in zip(Ys, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
