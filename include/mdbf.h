@@ -123,8 +123,9 @@ int mdbf_unpack(const void* packed_dev, int rows, int cols,
 int mdbf_pad_envelope(const void* env_dev, int rows, int l, int dtype, void* out_dev, int l_to, void* stream);
 
 /* ---- forward product ------------------------------------------------------------------
- * Workspace bytes needed by mdbf_forward for T tokens (room for the inner vector z in fp32, and for the
- * scaled activations of few-token calls). */
+ * Workspace bytes needed by mdbf_forward for T tokens (room for the inner vector z in fp32, for the
+ * scaled activations of few-token calls, and for the partial sums of a one-token call).  Host arithmetic
+ * only: the same value on every machine. */
 int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out);
 
 /* Y[b,:] = What X[b,:] for b < T.
@@ -133,9 +134,13 @@ int mdbf_workspace_bytes(const mdbf_desc_t* desc, int T, size_t* bytes_out);
  *   Y_dev  T x m row-major, leading dimension ldy >= m (elements of y_dtype); overwritten
  *   workspace_dev / workspace_bytes  caller-owned scratch, >= mdbf_workspace_bytes()
  * Default arithmetic: fp32 accumulation on the matrix cores.  One token: z kept in fp32; the l-way
- * scaled activations (b^(s) o x and q^(t) o z) are quantised once -- to fp16, or, in the block-scaled
- * variant the library takes for large plans, to three fp6 limbs under a shared power-of-two scale per 32
- * values (about 13 bits) -- and contracted with the sign words.  Two tokens or more: the factors
+ * scaled activations (b^(s) o x and q^(t) o z) are quantised once -- to three fp6 limbs under a shared
+ * power-of-two scale per 32 values (about 13 bits; the block-scaled variant, taken by single calls and large
+ * plans of rank 8 or 16 with fp16 envelopes), or to fp16 (small plans, MDBF_FLAG_FP16_STAGED) -- and
+ * contracted with the sign words.  A single one-token call of the block-scaled variant is two launches: each
+ * factor's contraction is split across workgroups (a layer by itself cannot fill the device otherwise) and
+ * the fp32 partial sums are added in a fixed order, so repeated calls return the same bits; they differ in
+ * the last bits from what a plan returns for the same layer (another fixed order).  Two tokens or more: the factors
  * S_A o (A Q^T), S_B o (G B^T) are rebuilt piece by piece in fp16 and applied as dense products to the
  * fp16-rounded activations (x and z; z is stored in fp16 between the two products).  Magnitudes above
  * 65504 in those fp16 quantities overflow.

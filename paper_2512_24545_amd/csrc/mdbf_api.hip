@@ -63,7 +63,34 @@ bool use_mx(const StageProb& p, uint32_t flags) { return !(flags & MDBF_FLAG_FP1
 bool mx_worthwhile(long launch_tiles) {
   return launch_tiles >= (long)mx_item_tiles() * (long)mx_max_workgroups();
 }
-size_t layer_ws_bytes(const mdbf_desc_t* d, int T) { return z_bytes(d, T) + xs1_bytes(d, T) + xs2_bytes(d, T); }
+size_t plan_layer_ws_bytes(const mdbf_desc_t* d, int T) { return z_bytes(d, T) + xs1_bytes(d, T) + xs2_bytes(d, T); }
+
+// A single call with one token splits the contraction of each factor across workgroups (split_geom); its
+// partial sums and the completion counters of the second factor lie behind the plan-style workspace.
+bool wants_split(const mdbf_desc_t* d, int T) {
+  return T == 1 && (d->l == 16 || d->l == 8) && d->env_dtype == MDBF_F16 &&
+         !(d->flags & (MDBF_FLAG_PRECISE | MDBF_FLAG_FP16_STAGED));
+}
+struct SplitLayout {
+  SplitGeom g[2];
+  int64_t ld[2];                 // floats between the partial vectors of factor 1 / 2
+  size_t part_off[2], ctr_off, bytes;   // offsets from the start of the split region
+};
+SplitLayout split_layout(const mdbf_desc_t* d) {
+  SplitLayout L;
+  L.g[0] = split_geom(num_tiles(d->k), num_blocks(d->n));
+  L.g[1] = split_geom(num_tiles(d->m), num_blocks(d->k));
+  L.ld[0] = (int64_t)align_up((size_t)d->k, 64);
+  L.ld[1] = (int64_t)align_up((size_t)d->m, 64);
+  L.part_off[0] = 0;
+  L.part_off[1] = align_up((size_t)L.g[0].nsplit * (size_t)L.ld[0] * 4u, 256);
+  L.ctr_off = L.part_off[1] + align_up((size_t)L.g[1].nsplit * (size_t)L.ld[1] * 4u, 256);
+  L.bytes = L.ctr_off + align_up((size_t)L.g[1].ngroup * 4u, 256);
+  return L;
+}
+size_t layer_ws_bytes(const mdbf_desc_t* d, int T) {
+  return plan_layer_ws_bytes(d, T) + (wants_split(d, T) ? split_layout(d).bytes : 0);
+}
 
 int check_layer(const mdbf_desc_t* d, const void* SA, const void* SB, const mdbf_env_t* env, const void* X,
                 int64_t ldx, void* Y, int64_t ldy, int T) {
@@ -228,6 +255,20 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
   StageProb sp[2];
   make_stages(desc, SA_packed_dev, SB_packed_dev, env, X_dev, ldx, Y_dev, ldy, T, workspace_dev, sp);
   hipStream_t s = (hipStream_t)stream;
+  if (wants_split(desc, T) && stage_is_split(sp[0]) && stage_is_split(sp[1])) {
+    // two launches, no scale-in launch: the second factor's workgroups add up the first factor's partial sums
+    const SplitLayout L = split_layout(desc);
+    unsigned char* base = (unsigned char*)workspace_dev + plan_layer_ws_bytes(desc, T);
+    float* part1 = (float*)(base + L.part_off[0]);
+    float* part2 = (float*)(base + L.part_off[1]);
+    uint32_t* ctr = (uint32_t*)(base + L.ctr_off);
+    const bool direct1 = L.g[0].nsplit == 1;         // then z itself is written and read
+    int e = launch_stage_mx_split(&sp[0], L.g[0], nullptr, 0, 0, part1, L.ld[0], nullptr, ctr, L.g[1].ngroup, s);
+    if (e) return hip_fail(e);
+    e = launch_stage_mx_split(&sp[1], L.g[1], direct1 ? nullptr : part1, direct1 ? 0 : L.g[0].nsplit, L.ld[0], part2,
+                              L.ld[1], ctr, nullptr, 0, s);
+    return hip_fail(e);
+  }
   {
     bool both_gemm = !(desc->flags & MDBF_FLAG_PRECISE) && T >= kGemmMinTokensSingle;
     for (int i = 0; i < 2; ++i)
@@ -408,7 +449,7 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
     precise += (L->desc.flags & MDBF_FLAG_PRECISE) ? 1 : 0;
     tiles[0] += num_tiles(L->desc.k);
     tiles[1] += num_tiles(L->desc.m);
-    ws += layer_ws_bytes(&L->desc, L->T);
+    ws += plan_layer_ws_bytes(&L->desc, L->T);
   }
   if (precise != 0 && precise != count) return MDBF_EUNSUPPORTED;  // all or none
   memset(h, 0, sizeof(*h));
@@ -511,7 +552,7 @@ int mdbf_batch_plan_build(int count, const mdbf_layer_t* layers, void* workspace
     make_stages(&L->desc, L->SA_packed_dev, L->SB_packed_dev, &L->env, L->X_dev, L->ldx, L->Y_dev, L->ldy, L->T,
                 (unsigned char*)workspace_dev + zoff, sp);
     if (h.gemm) half_intermediate(sp);
-    zoff += layer_ws_bytes(&L->desc, L->T);
+    zoff += plan_layer_ws_bytes(&L->desc, L->T);
     for (int s = 0; s < 2; ++s) {
       probs[s][(size_t)i] = sp[s];
       if (!stage_is_fast(sp[s])) fast[s] = 0;

@@ -163,6 +163,22 @@ int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, con
 // items_dev null: one problem (`single`), items are cut on the fly
 // single->l = the envelope rank of the launch (16 or 8; a plan's problems all have the same)
 int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s);
+// Split variant of the block-scaled kernel for one small problem with one token: workgroup (g, s) takes row
+// tiles 8g .. 8g + 7 and `bs` blocks of the contraction dimension and builds its activation records itself;
+// the partial sums of the nsplit workgroups of a tile group are added in a fixed order, by the reader
+// (part_in of the next launch) or by the last workgroup of the group to finish (counters).
+struct SplitGeom {
+  int bs, nsplit, ngroup;
+};
+SplitGeom split_geom(int ntiles, int KB);    // host arithmetic only: the same on every machine
+bool stage_is_split(const StageProb& p);     // l == 16 or 8, fp16 envelopes, one token
+// part_in (or null: p->vin): nsplit_in vectors part_in_ld apart whose sum is the activation vector.
+// part_out: g.nsplit vectors part_out_ld apart (unused when g.nsplit == 1: the result goes to p->out).
+// counters (or null): g.ngroup zeroed words; with them the launch itself stores the sums to p->out.
+// clear (or null): nclear words this launch sets to zero.
+int launch_stage_mx_split(const StageProb* p, const SplitGeom& g, const float* part_in, int nsplit_in,
+                          int64_t part_in_ld, float* part_out, int64_t part_out_ld, uint32_t* counters,
+                          uint32_t* clear, int nclear, hipStream_t s);
 constexpr int kMaxPreTokens = 16;   // token counts up to this use the scale-in kernel
 // true if the fast matrix-core variant can run the problem (l == 16, fp16 envelopes, K % 8 == 0,
 // 16-byte aligned activation rows); otherwise the general variant is used

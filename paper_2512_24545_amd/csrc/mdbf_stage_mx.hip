@@ -160,11 +160,20 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool RANK8>
-__device__ __forceinline__ void prep_record(const StageProb& p, int unit, int lane, const PrepInput& in, float* pr) {
-  const int b = unit / p.KB, q = unit - b * p.KB;
+// one 16-, 8- or 4-byte piece of a record: to global memory with the non-temporal hint (the records are read
+// once, by the product launch that follows; with plain stores the write-back of 40 to 55 MB of dirty lines
+// runs into that launch: measured on the 336-layer workload, 257 -> 248 us per step with the hint), or to LDS
+template <bool TO_LDS, class V>
+__device__ __forceinline__ void record_store(unsigned char* base, int index, V v) {
+  if constexpr (TO_LDS) ((MDBF_LDS V*)base)[index] = v;
+  else __builtin_nontemporal_store(v, &((MDBF_GLOBAL V*)base)[index]);
+}
+
+// the record of block q of the problem's contraction dimension, from the inputs `in`, written to `blk`
+template <bool RANK8, bool TO_LDS>
+__device__ __forceinline__ void prep_record_to(const StageProb& p, int q, int lane, const PrepInput& in, float* pr,
+                                               unsigned char* blk) {
   const int kg = lane >> 4, n = lane & 15;
-  unsigned char* blk = (unsigned char*)p.xs + ((size_t)b * p.KB + q) * (size_t)kBlockBytes;
   const bool has_modes = (lane & 1) < (p.l >> 3);
 
   // ---- 1. products
@@ -248,21 +257,25 @@ __device__ __forceinline__ void prep_record(const StageProb& p, int unit, int la
       a.x = slot[L][0]; a.y = slot[L][1]; a.z = slot[L][2]; a.w = slot[L][3];
       u32x2 bpart;
       bpart.x = slot[L][4]; bpart.y = slot[L][5];
-      // Non-temporal stores: the records are read once, by the product launch that follows.  With plain stores
-      // the write-back of 40 to 55 MB of dirty lines runs into that launch (measured on the 336-layer
-      // workload: 257 -> 248 us per step with the hint).
-      __builtin_nontemporal_store(a, &((MDBF_GLOBAL u32x4*)(blk + L * kLimbBytes))[lane]);
-      __builtin_nontemporal_store(bpart, &((MDBF_GLOBAL u32x2*)(blk + L * kLimbBytes + 64 * 16))[lane]);
+      record_store<TO_LDS>(blk + L * kLimbBytes, lane, a);
+      record_store<TO_LDS>(blk + L * kLimbBytes + 64 * 16, lane, bpart);
     }
   }
-  __builtin_nontemporal_store(e0 | (e1 << 8) | ((uint32_t)(E + 119) << 16),
-                              &((MDBF_GLOBAL uint32_t*)(blk + kScaleOff))[lane]);
+  record_store<TO_LDS>(blk + kScaleOff, lane, e0 | (e1 << 8) | ((uint32_t)(E + 119) << 16));
   if (upper) part = 0.f;   // the column sum of a mode is stored once
 
   // ---- 3. column sums of the block
   part += __shfl_xor(part, 16);
   part += __shfl_xor(part, 32);
-  if (lane < 16) __builtin_nontemporal_store(part, &((MDBF_GLOBAL float*)(blk + kColsumOff))[lane]);
+  if (lane < 16) record_store<TO_LDS>(blk + kColsumOff, lane, part);
+}
+
+// record of unit (token, block) of the problem's activation stream in global memory
+template <bool RANK8>
+__device__ __forceinline__ void prep_record(const StageProb& p, int unit, int lane, const PrepInput& in, float* pr) {
+  const int b = unit / p.KB, q = unit - b * p.KB;
+  unsigned char* blk = (unsigned char*)p.xs + ((size_t)b * p.KB + q) * (size_t)kBlockBytes;
+  prep_record_to<RANK8, false>(p, q, lane, in, pr, blk);
 }
 
 template <bool RANK8>
@@ -654,6 +667,164 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Split variant for one small problem (a single layer, one token): 64-tile items would leave most of the
+// device idle and a workgroup would walk the whole contraction dimension by itself.  Here workgroup (g, s)
+// takes row tiles 8g .. 8g + 7 (one per wave) and blocks [s * bs, s * bs + bs) of the contraction
+// dimension, builds the records of its blocks in LDS itself (no scale-in launch), contracts, applies the
+// envelope rows and ends up with one partial sum per row: the envelope-accumulate of Eq. "me-dbf-expand"
+// is linear in P, so 16 floats per tile leave the workgroup instead of 16 x 16.
+//  * first factor: the partial sums go to part_out[s][row]; the second factor's workgroups add them up in
+//    the order of s as they load their activations (vin = the sum), so no launch or wait lies between.
+//  * second factor: the partial sums are written through to memory (device-scope stores) and a counter per
+//    tile group is raised; whichever workgroup raises it to nsplit adds the nsplit partial sums of the
+//    group's rows in the order of s and stores the result.  Nobody waits for anybody, and the order of the
+//    additions is fixed: the result is the same bits every time.
+// The counters are cleared by the first factor's launch of the same call.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kSplitWaves = 8;      // row tiles per workgroup
+constexpr int kSplitMaxBs = 4;      // blocks per workgroup at most (one record-building wave each)
+
+// sum of count values `ld` floats apart, added in index order.  The loads go out eight at a time before the
+// first addition (each one is a trip to memory: partial sums are never in this workgroup's caches).
+// COHERENT: written by other workgroups of the same launch with device-scope stores; read the same way.
+template <bool COHERENT>
+__device__ __forceinline__ float ordered_sum(const MDBF_GLOBAL float* first, int count, int64_t ld) {
+  float sum = 0.f;
+  for (int t0 = 0; t0 < count; t0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const MDBF_GLOBAL float* src = first + (size_t)min(t0 + j, count - 1) * ld;
+      v[j] = COHERENT ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (t0 + j < count) sum += v[j];
+  }
+  return sum;
+}
+
+struct SplitArgs {
+  StageProb p;
+  int32_t bs, nsplit;               // blocks per workgroup; workgroups per tile group
+  const float* part_in;             // vin[j] = sum over s < nsplit_in of part_in[s * part_in_ld + j]; null: p.vin
+  int64_t part_in_ld;
+  float* part_out;                  // [nsplit][part_out_ld] partial sums (unused when nsplit == 1)
+  int64_t part_out_ld;
+  uint32_t* counters;               // one per tile group: this launch finishes its rows itself; null: the reader adds
+  uint32_t* clear;                  // counters to clear for the launch that follows (null: none)
+  int32_t nsplit_in, nclear;
+};
+
+template <bool RANK8>
+__global__ __launch_bounds__(64 * kSplitWaves) void stage_mx_split_kernel(SplitArgs a) {
+  __shared__ __attribute__((aligned(16))) unsigned char recs[kSplitMaxBs * kBlockBytes];
+  __shared__ __attribute__((aligned(16))) float prod[kSplitMaxBs][128 * kProdStride];
+  __shared__ uint32_t is_last;
+  constexpr int RANK = RANK8 ? 8 : 16;
+  constexpr int NL = RANK8 ? 2 : 3;
+  const StageProb& p = a.p;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kg = lane >> 4, n = lane & 15;
+  const int g = (int)blockIdx.x / a.nsplit, s = (int)blockIdx.x - g * a.nsplit;
+  const int q0 = s * a.bs;
+  const int nb = min(a.bs, p.KB - q0);                 // >= 1: nsplit = ceil(KB / bs)
+  if (a.clear && blockIdx.x == 0)
+    for (int i = tid; i < a.nclear; i += 64 * kSplitWaves)
+      __hip_atomic_store((MDBF_GLOBAL uint32_t*)a.clear + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // ---- this wave's tile: sign words of the workgroup's blocks and the envelope rows (issued first)
+  const int tile = g * kSplitWaves + wave;
+  const int tile_c = min(tile, p.ntiles - 1);
+  uint32_t w[kSplitMaxBs];
+#pragma unroll
+  for (int i = 0; i < kSplitMaxBs; ++i)
+    w[i] = ((g_u32_ptr)p.S)[word_offset(tile_c, min(q0 + i, p.KB - 1), lane, p.KB, p.ntiles)];
+  _Float16 ev[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = min(tile_c * kTileRows + 4 * kg + i, p.rows - 1);
+    ev[i] = ((const MDBF_GLOBAL _Float16*)p.Eout)[(size_t)row * RANK + (n & (RANK - 1))];
+  }
+
+  // ---- records of the workgroup's blocks: wave i builds block q0 + i
+  if (wave < nb) {
+    const int q = q0 + wave;
+    PrepInput in = prep_load(p, q, lane);              // (token 0; with part_in the activations read here are not used)
+    StageProb pp = p;
+    if (a.part_in) {
+      pp.vin_dt = MDBF_F32;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int kc = min(q * kBlockCols + (lane >> 1) + 32 * i, p.K - 1);
+        const float sum = ordered_sum<false>((g_f32_ptr)a.part_in + kc, a.nsplit_in, a.part_in_ld);
+        in.xbits[i] = __builtin_bit_cast(uint32_t, sum);
+      }
+    }
+    prep_record_to<RANK8, true>(pp, q, lane, in, prod[wave], recs + wave * kBlockBytes);
+  }
+  __syncthreads();
+
+  // ---- contraction of the tile against the records
+  const SignConsts sconst = sign_consts();
+  floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+  float colsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < kSplitMaxBs; ++i) {
+    if (i < nb) {
+      const unsigned char* rec = recs + i * kBlockBytes;
+      const uint32_t scales = reinterpret_cast<const uint32_t*>(rec + kScaleOff)[lane];
+      colsum += reinterpret_cast<const float*>(rec + kColsumOff)[n];
+      const v8i sa = sign_operand(w[i], sconst);
+#pragma unroll
+      for (int L = 0; L < NL; ++L) {
+        const u32x4 x = reinterpret_cast<const u32x4*>(rec + L * kLimbBytes)[lane];
+        const u32x2 y = reinterpret_cast<const u32x2*>(rec + L * kLimbBytes + 64 * 16)[lane];
+        v8i limb;
+        limb[0] = (int)x.x; limb[1] = (int)x.y; limb[2] = (int)x.z; limb[3] = (int)x.w;
+        limb[4] = (int)y.x; limb[5] = (int)y.y; limb[6] = 0; limb[7] = 0;
+        acc = mx_mfma(sa, limb, acc, L, scales);
+      }
+    }
+  }
+
+  // ---- envelope rows: fix-up, accumulate over the modes; one partial sum per row
+  float v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = row16_sum((float)ev[i] * (colsum - 2.f * acc[i]));
+  const int sel = n & 3;
+  const float res = sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3];
+  const int row = tile * kTileRows + 4 * kg + n;
+  const bool mine = n < 4 && tile < p.ntiles && row < p.rows;
+  if (a.nsplit == 1) {
+    if (mine) emit_result(p.out, row, p.out_dt, res, p.flags);
+    return;
+  }
+  // read by another workgroup, possibly on another XCD: written through to memory
+  if (mine)
+    __hip_atomic_store((MDBF_GLOBAL float*)a.part_out + (size_t)s * a.part_out_ld + row, res, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  if (!a.counters) return;
+
+  // ---- the last workgroup of the tile group adds the partial sums up
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's partial sums are in memory
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t old = __hip_atomic_fetch_add((MDBF_GLOBAL uint32_t*)a.counters + g, 1u, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+    is_last = (old + 1u == (uint32_t)a.nsplit) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (!is_last) return;
+  const int frow = g * (kSplitWaves * kTileRows) + tid;
+  if (tid < kSplitWaves * kTileRows && frow < p.rows) {
+    const float sum = ordered_sum<true>((g_f32_ptr)a.part_out + frow, a.nsplit, a.part_out_ld);
+    emit_result(p.out, frow, p.out_dt, sum, p.flags);
+  }
+}
+
 static int max_workgroups() { return kWgsPerCu * compute_units(); }
 
 template <bool BATCH, int RANK>
@@ -714,6 +885,48 @@ int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* sing
     return mx::launch_b<false>(nullptr, nitems, single, s);
   }
   return mx::launch_b<true>(items_dev, nitems, single, s);
+}
+
+SplitGeom split_geom(int ntiles, int KB) {
+  // enough workgroups for a device of 256 compute units whatever the device: the workspace layout follows
+  // from these numbers and must not depend on where it is computed
+  constexpr int kTargetWgs = 256;
+  SplitGeom g;
+  g.ngroup = (ntiles + mx::kSplitWaves - 1) / mx::kSplitWaves;
+  const int want = (kTargetWgs + g.ngroup - 1) / g.ngroup;
+  int bs = (KB + want - 1) / want;
+  // at most eight partial sums per row where the block limit allows: whoever adds them up fetches eight at a
+  // time, and every further round is another trip to memory
+  if (bs < (KB + 7) / 8) bs = (KB + 7) / 8;
+  bs = bs < 1 ? 1 : bs > mx::kSplitMaxBs ? mx::kSplitMaxBs : bs;
+  g.bs = bs;
+  g.nsplit = (KB + bs - 1) / bs;
+  return g;
+}
+
+bool stage_is_split(const StageProb& p) {
+  return (p.l == 16 || p.l == 8) && p.env_dt == MDBF_F16 && p.T == 1 && p.KB >= 1 && p.ntiles >= 1;
+}
+
+int launch_stage_mx_split(const StageProb* p, const SplitGeom& g, const float* part_in, int nsplit_in,
+                          int64_t part_in_ld, float* part_out, int64_t part_out_ld, uint32_t* counters,
+                          uint32_t* clear, int nclear, hipStream_t s) {
+  mx::SplitArgs a;
+  a.p = *p;
+  a.bs = g.bs;
+  a.nsplit = g.nsplit;
+  a.part_in = part_in;
+  a.part_in_ld = part_in_ld;
+  a.part_out = part_out;
+  a.part_out_ld = part_out_ld;
+  a.counters = counters;
+  a.clear = clear;
+  a.nsplit_in = nsplit_in;
+  a.nclear = nclear;
+  const dim3 grid((unsigned)(g.ngroup * g.nsplit)), block(64 * mx::kSplitWaves);
+  if (p->l == 8) hipLaunchKernelGGL(mx::stage_mx_split_kernel<true>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(mx::stage_mx_split_kernel<false>, grid, block, 0, s, a);
+  return (int)hipGetLastError();
 }
 
 }  // namespace mdbf

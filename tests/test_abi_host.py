@@ -92,6 +92,23 @@ def test_workspace_bytes():
     assert mb.lib().mdbf_workspace_bytes(C.byref(d), 0, C.byref(out)) == -1
 
 
+def test_workspace_of_a_one_token_call_holds_its_partial_sums():
+    """A single one-token call of rank 16 / fp16 envelopes splits each factor's contraction across workgroups:
+    its workspace has room for the partial sums (4096x4096, k = 2656: 21 tile groups x 8 splits of the first
+    factor, 32 x 7 of the second) and the second factor's completion counters, on top of what the same layer
+    needs with MDBF_FLAG_FP16_STAGED (no split).  Other token counts and the fp32 path are not affected."""
+    split = mb.Desc(4096, 4096, 2656, 16, mb.MDBF_F16, mb.MDBF_F16, mb.MDBF_F32, 0)
+    staged = mb.Desc(4096, 4096, 2656, 16, mb.MDBF_F16, mb.MDBF_F16, mb.MDBF_F32, mb.MDBF_FLAG_FP16_STAGED)
+    extra = mb.mdbf_workspace_bytes(split, 1) - mb.mdbf_workspace_bytes(staged, 1)
+    ld1, ld2 = 2688, 4096                      # k and m rounded up to 64 floats
+    assert extra == 8 * ld1 * 4 + 7 * ld2 * 4 + 256
+    assert mb.mdbf_workspace_bytes(split, 2) == mb.mdbf_workspace_bytes(staged, 2)
+    precise = mb.Desc(4096, 4096, 2656, 16, mb.MDBF_F16, mb.MDBF_F16, mb.MDBF_F32, mb.MDBF_FLAG_PRECISE)
+    f32env = mb.Desc(4096, 4096, 2656, 16, mb.MDBF_F16, mb.MDBF_F32, mb.MDBF_F32, 0)
+    for d in (precise, f32env):
+        assert mb.mdbf_workspace_bytes(d, 1) < mb.mdbf_workspace_bytes(split, 1)
+
+
 def test_pack_argument_errors():
     L = mb.lib()
     assert L.mdbf_pack(None, 4, 4, 4, FAKE, 1 << 20, None) == -1

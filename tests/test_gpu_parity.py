@@ -221,9 +221,14 @@ def test_block_scaled_batch_equals_single_calls(gpu):
     plan = mb.BatchPlan(layers, Xs, Ys, block_scaled=True)
     plan.run()
     torch.cuda.synchronize()
-    for Yb, Y1, ref in zip(Ys, singles, refs):
+    for (m, n, k, T), Yb, Y1, ref in zip(specs, Ys, singles, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
-        assert torch.equal(Yb, Y1)
+        if T == 1:
+            # a single call with one token splits the contraction across workgroups: fp32 partial sums added
+            # in another (fixed) order, so z differs in its last bits and a few of its limbs round the other way
+            assert orc.max_rel_error(Yb.cpu().numpy(), Y1.cpu().numpy().astype(np.float64)) <= 5e-4
+        else:
+            assert torch.equal(Yb, Y1)
 
 
 # ---------------------------------------------------------------- LLaMA-7B shaped layers
@@ -255,6 +260,24 @@ def test_determinism(gpu):
     Y2 = mb.mdbf_forward(dl, Xd)
     torch.cuda.synchronize()
     assert torch.equal(Y1, Y2)
+
+
+def test_determinism_of_the_split_contraction(gpu):
+    """One token: the contraction of each factor is split across workgroups and the partial sums are added in a
+    fixed order (by the reader for the first factor, by the last workgroup to finish for the second), so
+    repeated calls give the same bits, whichever workgroup finishes last."""
+    torch, mb = gpu
+    for seed, (m, n, k, l) in enumerate([(4096, 4096, 2656, 16), (1100, 1030, 2105, 16), (530, 2104, 1104, 8)]):
+        L = synth.make_layer(m, n, k, l, seed=70 + seed, env_dtype="f16", env_kind="llama", signed_env=True)
+        X = synth.make_activations(n, 1, seed=80 + seed, x_dtype="f16")
+        dl = mb.DeviceLayer.from_host(L)
+        Xd = _to_dev(torch, X, "f16")
+        first = mb.mdbf_forward(dl, Xd, y_dtype="f32").clone()
+        for _ in range(20):
+            again = mb.mdbf_forward(dl, Xd, y_dtype="f32")
+            assert torch.equal(first, again)
+        ref = orc.forward_factored(*_oracle_args(L), X)
+        assert orc.max_rel_error(first.cpu().numpy(), ref) <= TOL
 
 
 # ---------------------------------------------------------------- many layers in one launch pair
@@ -289,13 +312,15 @@ def test_batch_mixed_layers(gpu):
 
 
 def test_batch_fast_layers_equal_single_calls(gpu):
-    """All layers l = 16 / fp16: the plan and the single calls run the same kernel, bit for bit."""
+    """All layers l = 16 / fp16, one token.  A plan this small runs the fp16-staged kernel, the single calls the
+    block-scaled one with the contraction split across workgroups: the two quantise the staged activations
+    differently (fp16 against three fp6 limbs)."""
     torch, mb = gpu
     specs = [(530, 2104, 1104, 16), (4096, 4096, 2656, 16), (272, 1032, 4096, 16), (4096, 4096, 2656, 16)]
     Ys, singles, refs = _batch_case(gpu, specs, tokens=lambda i: 1)
     for Yb, Y1, ref in zip(Ys, singles, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
-        assert torch.equal(Yb, Y1)
+        assert orc.max_rel_error(Yb.cpu().numpy(), Y1.cpu().numpy().astype(np.float64)) <= 5e-4
 
 
 def test_plan_of_several_tokens_equals_single_calls(gpu):
