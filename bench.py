@@ -143,6 +143,9 @@ def main():
     ap.add_argument("--copies", type=int, default=336, help="independent layers per step (336 x 3.17 MB > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the graph / hot / latency side measurements")
+    ap.add_argument("--quick", action="store_true",
+                    help="side measurements with a twentieth of their repetitions (for runs under hardware counters, "
+                         "where every dispatch is serialised)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy, the known-size reference for the HBM traffic counters")
     a = ap.parse_args()
@@ -192,7 +195,7 @@ def main():
 
     # ---- roofline of the dominant kernel: the product kernel (one launch per factor, two per step), timed
     #      by itself over the same number of steps; the scale-in results of the last full step stay valid
-    part_steps = max(a.steps, 200)
+    part_steps = a.steps if a.quick else max(a.steps, 200)
     e0, e1 = ev(), ev()
     preheat(torch, lambda: plan.run_part(3, 2), a.preheat_ms)
     e0.record()
@@ -277,7 +280,8 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         extras["hot_in_cache"] = {"GB/s": 64 * bytes_call * 100 / e0.elapsed_time(e1) / 1e6}
-        # (3) latency of one isolated call (two launches), stream-ordered
+        # (3) latency of one isolated call (two launches: each factor's contraction split across workgroups),
+        #     stream-ordered
         e0.record()
         for _ in range(200):
             mb.mdbf_forward(layers[1], Xs[1], y_dtype="f16", Y=Ys[1], workspace=ws[1])
@@ -310,8 +314,9 @@ def main():
                                  "peak": 2500.0, "unit": "TFLOP/s", "frac": issued / ms / 1e9 / 2500.0,
                                  "flops_per_call": issued}}
 
-        extras["decode_T16_mlp_gate"] = time_call(11008, 4096, 4096, 16, 300)
-        extras["prefill_T2048_attn"] = time_call(M, N, K, 2048, 300)
+        q = 20 if a.quick else 1
+        extras["decode_T16_mlp_gate"] = time_call(11008, 4096, 4096, 16, 300 // q)
+        extras["prefill_T2048_attn"] = time_call(M, N, K, 2048, 300 // q)
         # matrix-core busy share of the prefill kernels, from the committed counter run (profiles/)
         cpath = os.path.join(ROOT, "profiles", "counters_prefill.json")
         if os.path.exists(cpath):
@@ -346,8 +351,8 @@ def main():
                     "us_per_layer": ms * 1e3 / len(pl), "GB/s": nbytes / ms / 1e6,
                     "pct_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS * 100.0, "max_rel_err_vs_oracle": max(errs)}
 
-        extras["mlp_plan_T1"] = time_mlp_plan(1, 300)
-        extras["mlp_plan_T16"] = time_mlp_plan(16, 150)
+        extras["mlp_plan_T1"] = time_mlp_plan(1, 300 // q)
+        extras["mlp_plan_T16"] = time_mlp_plan(16, 150 // q)
 
     out = {
         "metric": "MDBF decode GEMV HBM GB/s (% peak) + prefill TFLOP/s, LLaMA-7B shapes",
