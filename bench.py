@@ -143,6 +143,8 @@ def main():
     ap.add_argument("--copies", type=int, default=336, help="independent layers per step (336 x 3.17 MB > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the graph / hot / latency side measurements")
+    ap.add_argument("--fp16-staged", action="store_true",
+                    help="headline plan on the fp16-staged kernel (MDBF_FLAG_FP16_STAGED) instead of the block-scaled one")
     ap.add_argument("--quick", action="store_true",
                     help="side measurements with a twentieth of their repetitions (for runs under hardware counters, "
                          "where every dispatch is serialised)")
@@ -168,7 +170,7 @@ def main():
         del src, dst
 
     layers, Xs, Ys = make_device_layers(torch, mb, a.copies, seed=2)
-    plan = mb.BatchPlan(layers, Xs, Ys)
+    plan = mb.BatchPlan(layers, Xs, Ys, fp16_staged=a.fp16_staged)
     bytes_call = algorithmic_bytes(M, N, K, L)
     bytes_step = bytes_call * a.copies
 
@@ -215,7 +217,9 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic_attn_decode.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f)["hbm_bytes_per_layer_per_launch"] * a.copies
+            rec = json.load(f)
+        if rec["kernel"].startswith(plan.kernel(1)):     # the record is of the block-scaled kernel
+            traffic = rec["hbm_bytes_per_layer_per_launch"] * a.copies
     # the share of a layer's algorithmic bytes that the product kernel itself moves, averaged over its two
     # launches per step: the packed signs of the factor, the envelope factor on its output side (G resp. A)
     # and y; the other envelope factor (B resp. Q) and x are read by the scale-in kernel
