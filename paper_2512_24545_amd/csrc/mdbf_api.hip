@@ -485,7 +485,16 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
   long nitems[2] = {0, 0};
   for (int s = 0; s < 2; ++s) {
     h->mx[s] = mx[s];
-    h->tiles_per_item[s] = h->gemm ? gemm_tiles_per_item() : mx[s] ? mx_item_tiles() : tpi_fp16;
+    int tpi_mx = mx_item_tiles();
+    if (mx[s] && !h->gemm) {
+      std::vector<int> nt(count), kb(count);
+      for (int i = 0; i < count; ++i) {
+        nt[i] = num_tiles(s == 0 ? layers[i].desc.k : layers[i].desc.m);
+        kb[i] = num_blocks(s == 0 ? layers[i].desc.n : layers[i].desc.k) * layers[i].T;
+      }
+      tpi_mx = mx_pick_item_tiles(count, nt.data(), kb.data());
+    }
+    h->tiles_per_item[s] = h->gemm ? gemm_tiles_per_item() : mx[s] ? tpi_mx : tpi_fp16;
   }
   for (int i = 0; i < count; ++i) {
     nitems[0] += (num_tiles(layers[i].desc.k) + h->tiles_per_item[0] - 1) / h->tiles_per_item[0];

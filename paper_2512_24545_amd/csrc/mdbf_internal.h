@@ -154,14 +154,17 @@ size_t xs_bytes_for(int K, int T);
 // Block-scaled (MX) variant of the matrix-core kernel: signs as fp4, activations as three fp6 limbs with a
 // power-of-two scale per 32 values, written by its own scale-in kernel into the same xs buffer.
 size_t xs_bytes_for_mx(int K, int T);
-int mx_item_tiles();                         // row tiles per work item of this variant
+int mx_item_tiles();                         // row tiles per work item of this variant at most (64)
+// row tiles per work item (64, 56 or 48) for a launch over problems of ntiles[i] row tiles, kb[i] blocks
+int mx_pick_item_tiles(int count, const int* ntiles, const int* kb);
 int mx_max_workgroups();                     // workgroups of this variant the current device holds at once
 bool stage_is_mx(const StageProb& p);        // l == 16 or 8, fp16 envelopes, an xs buffer, few tokens
 // max_units: largest tokens x blocks of a problem of the launch
 int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, const StageProb* single,
                        hipStream_t s);
 // items_dev null: one problem (`single`), items are cut on the fly
-// single->l = the envelope rank of the launch (16 or 8; a plan's problems all have the same)
+// single->l = the envelope rank of the launch (16 or 8; a plan's problems all have the same); with items_dev,
+// single->ntiles = the row tiles per work item the plan was cut with (mx_pick_item_tiles)
 int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s);
 // Split variant of the block-scaled kernel for one small problem with one token: workgroup (g, s) takes row
 // tiles 8g .. 8g + 7 and `bs` blocks of the contraction dimension and builds its activation records itself;

@@ -49,28 +49,34 @@ constexpr int kScaleOff = 3 * kLimbBytes;      // 4608: 64 x 4 B, scale bytes of
 constexpr int kColsumOff = kScaleOff + 256;    // 4864: 16 fp32 column sums of the block
 constexpr int kBlockBytes = 5120;              // padded to a multiple of 1 KB (one loader instruction)
 
-// ---- main kernel geometry
+// ---- main kernel geometry.  R = row tiles per contraction wave: 8, or fewer when that leaves fewer unused
+// tile slots (a factor of 166 row tiles is three items of 56 tiles, not 64 + 64 + 38)
 constexpr int kComputeWaves = 8;
-constexpr int R = 64 / kComputeWaves;                  // row tiles per contraction wave
-constexpr int kItemTiles = kComputeWaves * R;          // row tiles per work item
-static_assert(kGroupTiles % kItemTiles == 0, "an item lies inside one group of the packed layout");
+constexpr int kMaxR = 8;
 constexpr int SB = 2;                                  // blocks per stage
 constexpr int kStages = 3;                             // ring depth
 constexpr int kStageXs = SB * kBlockBytes;
-constexpr int kStageSigns = kItemTiles * SB * 256;     // [block][tile][64 words]
-constexpr int kStageBytes = kStageXs + kStageSigns;
-constexpr int kEoBytes = kItemTiles * kTileRows * 32;  // envelope rows of an item (fp16, 16 modes)
-static_assert(kEoBytes <= kStageBytes, "the envelope rows travel in a stage of their own");
 constexpr int kXsInstr = kStageXs / 1024;              // loader instructions (64 lanes x 16 B each)
-constexpr int kSignInstr = kStageSigns / 1024;
-constexpr int kEoInstr = kEoBytes / 1024;
-constexpr int kSmemBytes = kStages * kStageBytes;
-constexpr int kWgsPerCu = (160 * 1024) / kSmemBytes;   // workgroups of this kernel a compute unit holds
 constexpr int kLoaderWaves = 2;                        // a wave keeps at most 63 loads in flight
 constexpr int kThreads = 64 * (kComputeWaves + kLoaderWaves);
-static_assert(kXsInstr % kLoaderWaves == 0 && kSignInstr % kLoaderWaves == 0 && kEoInstr % kLoaderWaves == 0,
-              "the loader waves split every stage evenly");
-static_assert(2 * (kXsInstr + kSignInstr) / kLoaderWaves <= 63, "two stages in flight must fit the counter");
+template <int R>
+struct Geo {
+  static constexpr int kItemTiles = kComputeWaves * R;          // row tiles per work item
+  static constexpr int kStageSigns = kItemTiles * SB * 256;     // [block][tile][64 words]
+  static constexpr int kStageBytes = kStageXs + kStageSigns;
+  static constexpr int kEoBytes = kItemTiles * kTileRows * 32;  // envelope rows of an item (fp16, 16 modes)
+  static constexpr int kSignInstr = kStageSigns / 1024;
+  static constexpr int kEoInstr = kEoBytes / 1024;
+  static constexpr int kSmemBytes = kStages * kStageBytes;
+  static constexpr int kSignInstrPerBlock = kItemTiles / 4 / kLoaderWaves;   // per loader wave
+  static_assert(kItemTiles % 4 == 0, "a loader instruction carries four whole tiles");
+  static_assert(kEoBytes <= kStageBytes, "the envelope rows travel in a stage of their own");
+  static_assert((160 * 1024) / kSmemBytes == 1, "one workgroup of this kernel per compute unit");
+  static_assert(kXsInstr % kLoaderWaves == 0 && kSignInstr % kLoaderWaves == 0 && kEoInstr % kLoaderWaves == 0,
+                "the loader waves split every stage evenly");
+  static_assert(2 * (kXsInstr + kSignInstr) / kLoaderWaves <= 63, "two stages in flight must fit the counter");
+};
+constexpr int kWgsPerCu = 1;                           // workgroups of the main kernel a compute unit holds
 
 // ---------------------------------------------------------------------------------------------------
 // fp6 e2m3: 1 sign, 2 exponent (bias 1), 3 mantissa bits: 0, 0.125 .. 0.875, 1 .. 1.875, 2 .. 3.75, 4 .. 7.5.
@@ -351,10 +357,9 @@ struct ItemInfo {
   int64_t out_ld;
   int rows, KB, T, out_dt, flags;
   int tile0, ntl;
-  int gt;                      // tiles in the packed layout's group that holds the item
 };
 
-template <bool BATCH>
+template <bool BATCH, int R>
 __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items, const StageProb& single, int item) {
   ItemInfo it;
   if (BATCH) {
@@ -371,7 +376,6 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.flags = w.p.flags;
     it.tile0 = w.tile0;
     it.ntl = w.ntiles;
-    it.gt = group_tiles(w.tile0, w.p.ntiles);
   } else {
     it.S = (const unsigned char*)single.S;
     it.xs = (const unsigned char*)single.xs;
@@ -383,9 +387,8 @@ __device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items
     it.T = single.T;
     it.out_dt = single.out_dt;
     it.flags = single.flags;
-    it.tile0 = item * kItemTiles;
-    it.ntl = min(kItemTiles, single.ntiles - it.tile0);
-    it.gt = group_tiles(it.tile0, single.ntiles);
+    it.tile0 = item * Geo<R>::kItemTiles;
+    it.ntl = min(Geo<R>::kItemTiles, single.ntiles - it.tile0);
   }
   return it;
 }
@@ -400,23 +403,33 @@ __device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t lane_
                                    STREAM ? kNonTemporal : 0);
 }
 
-// Lane offsets of the sign-word instructions of loader wave LW (it takes every kLoaderWaves-th instruction):
-// instruction 2 * jj + LW of a block carries tiles 4 * (2 * jj + LW) .. + 3, 16 bytes per lane; tiles past
-// the item's end repeat its last tile.  One set per item, so that an instruction costs no vector arithmetic.
-constexpr int kSignInstrPerBlock = kItemTiles / 4 / kLoaderWaves;
-template <int LW>
-__device__ __forceinline__ void sign_lane_offsets(const ItemInfo& it, int lane, uint32_t (&voff)[kSignInstrPerBlock]) {
+// Addresses of the sign-word instructions of loader wave LW (it takes every kLoaderWaves-th instruction):
+// instruction 2 * jj + LW of a block carries tiles 4 * (2 * jj + LW) .. + 3 of the item, 16 bytes per lane;
+// tiles past the item's end repeat its last tile.  An item may straddle the packed layout's groups of 64
+// tiles, an instruction's four tiles never do (items start at multiples of four tiles): per instruction, one
+// lane offset from the start of the packed matrix (block 0) and the byte distance between blocks, which is
+// that of the instruction's group.  One set per item, so that an instruction costs no vector arithmetic.
+template <int LW, int R>
+__device__ __forceinline__ void sign_lane_offsets(const ItemInfo& it, int lane, uint32_t (&voff)[R],
+                                                  uint32_t (&bstride)[R]) {
+  const int ntiles = num_tiles(it.rows);
 #pragma unroll
-  for (int jj = 0; jj < kSignInstrPerBlock; ++jj) {
-    const int trel = min((jj * kLoaderWaves + LW) * 4 + (lane >> 4), it.ntl - 1);
-    voff[jj] = (uint32_t)trel * 256u + (uint32_t)(lane & 15) * 16u;
+  for (int jj = 0; jj < R; ++jj) {
+    const int a = jj * kLoaderWaves + LW;
+    const int first = it.tile0 + min(4 * a, it.ntl - 1);                 // wave-uniform
+    const int g0 = first & ~(kGroupTiles - 1);
+    const int gt = min(kGroupTiles, ntiles - g0);
+    const int tile = it.tile0 + min(4 * a + (lane >> 4), it.ntl - 1);    // in the group of `first`
+    voff[jj] = ((uint32_t)g0 * (uint32_t)it.KB + (uint32_t)(tile - g0)) * 256u + (uint32_t)(lane & 15) * 16u;
+    bstride[jj] = (uint32_t)gt * 256u;
   }
 }
 
 // loader wave LW: blocks [q0, q0 + SB) of the item's tiles and of token b's activation stream into `stage`
-template <int LW>
+template <int LW, int R>
 __device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, unsigned char* stage, int lane,
-                                            const uint32_t (&voff)[kSignInstrPerBlock]) {
+                                            const uint32_t (&voff)[R], const uint32_t (&bstride)[R]) {
+  typedef Geo<R> G;
   // activation records: each record is five instructions; a block past the end repeats the last one
 #pragma unroll
   for (int j = 0; j < kXsInstr / kLoaderWaves; ++j) {
@@ -427,26 +440,26 @@ __device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, u
     const unsigned char* src = it.xs + ((size_t)b * it.KB + q) * (size_t)kBlockBytes;
     dma16<false>(src + part * 1024, (uint32_t)lane * 16u, stage + i * 1024);
   }
-  // sign words: in the packed layout the item's tiles of one block are contiguous (256 bytes per tile);
+  // sign words: in the packed layout the tiles of a group are contiguous per block (256 bytes per tile);
   // a block past the end repeats the last block
-  const unsigned char* ibase = it.S + tile_base_words(it.tile0, it.KB) * 4u;
-  const uint32_t bstride = (uint32_t)it.gt * 256u;
 #pragma unroll
-  for (int j = 0; j < kSignInstr / kLoaderWaves; ++j) {
+  for (int j = 0; j < G::kSignInstr / kLoaderWaves; ++j) {
     const int i = j * kLoaderWaves + LW;
-    const int blk = i / (kItemTiles / 4);
-    const unsigned char* bbase = ibase + (size_t)((uint32_t)min(q0 + blk, it.KB - 1) * bstride);
-    dma16<true>(bbase, voff[j % kSignInstrPerBlock], stage + kStageXs + i * 1024);
+    const int blk = i / (G::kItemTiles / 4);
+    const int jj = j % G::kSignInstrPerBlock;
+    // (one scalar multiplication and one vector addition per instruction; the whole offset fits 32 bits)
+    const uint32_t qoff = (uint32_t)min(q0 + blk, it.KB - 1) * bstride[jj];
+    dma16<true>(it.S, voff[jj] + qoff, stage + kStageXs + i * 1024);
   }
 }
 
 // loader: the item's envelope rows (RANK modes of fp16: 32 or 16 bytes per row, rows back to back) into
 // `stage`.  With 16-byte rows the second half of the instructions repeats the last row past the item's end.
-template <int RANK, int LW>
+template <int RANK, int LW, int R>
 __device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane) {
   constexpr int hsh = RANK >> 4;                // log2 of the 16-byte pieces per row: 1 or 0
 #pragma unroll
-  for (int j = 0; j < kEoInstr / kLoaderWaves; ++j) {
+  for (int j = 0; j < Geo<R>::kEoInstr / kLoaderWaves; ++j) {
     const int i = j * kLoaderWaves + LW;
     const int piece = 64 * i + lane;
     const int row = min(it.tile0 * kTileRows + (piece >> hsh), it.rows - 1);
@@ -456,6 +469,7 @@ __device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stag
 
 // What a contraction wave reads from LDS for one 128-column block of a stage: the block's three limbs with
 // their scales and column sum, and the sign words of the wave's R tiles.
+template <int R>
 struct BlockOperands {
   v8i limb[3];
   uint32_t scales;
@@ -464,10 +478,10 @@ struct BlockOperands {
 };
 
 // NL: record slots the matrix cores contract: 3 (rank 16), 2 (rank 8)
-template <int NL>
-__device__ __forceinline__ BlockOperands read_block(const unsigned char* stage, int blk, int lane, int n, int wave) {
+template <int NL, int R>
+__device__ __forceinline__ BlockOperands<R> read_block(const unsigned char* stage, int blk, int lane, int n, int wave) {
   const unsigned char* rec = stage + blk * kBlockBytes;
-  BlockOperands o;
+  BlockOperands<R> o;
 #pragma unroll
   for (int L = 0; L < NL; ++L) {
     const u32x4 a = reinterpret_cast<const u32x4*>(rec + L * kLimbBytes)[lane];
@@ -477,7 +491,7 @@ __device__ __forceinline__ BlockOperands read_block(const unsigned char* stage, 
   }
   o.scales = reinterpret_cast<const uint32_t*>(rec + kScaleOff)[lane];
   o.colsum = reinterpret_cast<const float*>(rec + kColsumOff)[n];
-  const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage + kStageXs) + blk * kItemTiles * 64 + lane;
+  const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage + kStageXs) + blk * Geo<R>::kItemTiles * 64 + lane;
 #pragma unroll
   for (int r = 0; r < R; ++r) o.w[r] = sw[(wave * R + r) * 64];
   return o;
@@ -486,24 +500,19 @@ __device__ __forceinline__ BlockOperands read_block(const unsigned char* stage, 
 // R tiles of this wave against the block's limbs.  Tiles past the item's end are contracted too (their
 // sign words repeat the last tile's; the results are not stored): skipping them costs more registers and
 // branches than it saves.
-template <int NL>
-__device__ __forceinline__ void contract_block(const BlockOperands& o, floatx4 (&acc)[R], float& colsum,
+template <int NL, int R>
+__device__ __forceinline__ void contract_block(const BlockOperands<R>& o, floatx4 (&acc)[R], float& colsum,
                                                const SignConsts& k) {
   colsum += o.colsum;
-  // eight tiles at a time (their expanded sign operands are 32 registers), limb outermost: consecutive
-  // instructions write different accumulators
+  // all tiles' sign operands first (4 R registers), limb outermost: consecutive instructions write different
+  // accumulators
+  v8i a[R];
 #pragma unroll
-  for (int h = 0; h < R; h += 8) {
-    v8i a[8];
+  for (int r = 0; r < R; ++r) a[r] = sign_operand(o.w[r], k);
 #pragma unroll
-    for (int r = 0; r < 8; ++r) a[r] = sign_operand(o.w[h + r], k);
+  for (int L = 0; L < NL; ++L) {
 #pragma unroll
-    for (int L = 0; L < NL; ++L) {
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        acc[h + r] = mx_mfma(a[r], o.limb[L], acc[h + r], L, o.scales);
-      }
-    }
+    for (int r = 0; r < R; ++r) acc[r] = mx_mfma(a[r], o.limb[L], acc[r], L, o.scales);
   }
 }
 
@@ -511,25 +520,26 @@ __device__ __forceinline__ void contract_block(const BlockOperands& o, floatx4 (
 // every token, ceil(KB / SB) contraction stages followed by one stage with the envelope rows; stage g lives
 // in ring slot g % kStages), two stages ahead of the contraction waves.  Barrier g opens stage g for them
 // and tells the loader that stage g - 1 has been drained, so that its slot can take stage g + 2.
-template <bool BATCH, int RANK, int LW>
+template <bool BATCH, int RANK, int LW, int R>
 __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, const StageProb& single, int item0,
                                             int i_hi, int stride, unsigned char* smem, int lane) {
+  typedef Geo<R> G;
   int item = item0;
-  ItemInfo it = load_item<BATCH>(items, single, item);
-  uint32_t voff[kSignInstrPerBlock];
-  sign_lane_offsets<LW>(it, lane, voff);
+  ItemInfo it = load_item<BATCH, R>(items, single, item);
+  uint32_t voff[R], bstride[R];
+  sign_lane_offsets<LW, R>(it, lane, voff, bstride);
   int b = 0, t = 0;                       // cursor: next stage to issue = stage t of (item, b)
   int nst = (it.KB + SB - 1) / SB;        // contraction stages of the cursor's unit
   bool more = true;                       // the cursor points at an existing stage
   int slot = 0;                           // ring slot of the next stage to issue
   int kind_prev = 0;                      // kind of the newest issued stage: 0 contraction, 1 envelope rows
   auto issue_next = [&]() {
-    unsigned char* stage = smem + slot * kStageBytes;
+    unsigned char* stage = smem + slot * G::kStageBytes;
     if (t < nst) {
-      issue_stage<LW>(it, b, t * SB, stage, lane, voff);
+      issue_stage<LW, R>(it, b, t * SB, stage, lane, voff, bstride);
       kind_prev = 0;
     } else {
-      issue_eo<RANK, LW>(it, stage, lane);
+      issue_eo<RANK, LW, R>(it, stage, lane);
       kind_prev = 1;
     }
     slot = (slot + 1 == kStages) ? 0 : slot + 1;
@@ -544,8 +554,8 @@ __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, 
         b = 0;
         item += stride;
         if (item < i_hi) {
-          it = load_item<BATCH>(items, single, item);
-          sign_lane_offsets<LW>(it, lane, voff);
+          it = load_item<BATCH, R>(items, single, item);
+          sign_lane_offsets<LW, R>(it, lane, voff, bstride);
           nst = (it.KB + SB - 1) / SB;
         } else {
           more = false;
@@ -560,8 +570,8 @@ __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, 
   for (;;) {
     // hand over the oldest outstanding stage: all but the newest stage's loads must have landed
     if (outstanding == 2) {
-      if (kind_prev == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kXsInstr + kSignInstr) / kLoaderWaves) : "memory");
-      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kEoInstr / kLoaderWaves) : "memory");
+      if (kind_prev == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kXsInstr + G::kSignInstr) / kLoaderWaves) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(G::kEoInstr / kLoaderWaves) : "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
@@ -579,7 +589,7 @@ __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, 
 // either way; with rank 8, column n < 8 carries limbs 1 and 3 of mode n and column n + 8 limb 2 of the same
 // mode (each column has its own scales), so a tile and block take two instructions instead of three; the
 // sum over the 16 columns in the epilogue, with mode n's envelope entry on both of its columns, joins them.
-template <bool BATCH, int RANK>
+template <bool BATCH, int RANK, int R>
 __global__ __launch_bounds__(kThreads)
 void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -605,15 +615,15 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   // both roles walk the same stage sequence (see loader_role); one barrier per stage
   if (wave >= kComputeWaves) {
     static_assert(kLoaderWaves == 2, "one instantiation of the loader role per loader wave");
-    if (wave == kComputeWaves) loader_role<BATCH, RANK, 0>(items, single, item0, i_hi, stride, smem, lane);
-    else loader_role<BATCH, RANK, 1>(items, single, item0, i_hi, stride, smem, lane);
+    if (wave == kComputeWaves) loader_role<BATCH, RANK, 0, R>(items, single, item0, i_hi, stride, smem, lane);
+    else loader_role<BATCH, RANK, 1, R>(items, single, item0, i_hi, stride, smem, lane);
     return;
   }
 
   // =========================== contraction waves ===========================
   const SignConsts sconst = sign_consts();
   int item = item0;
-  ItemInfo it = load_item<BATCH>(items, single, item);
+  ItemInfo it = load_item<BATCH, R>(items, single, item);
   int slot = 0;
   for (;;) {
     const int nr = max(0, min(R, it.ntl - wave * R));   // valid tiles of this wave (it owns tiles wave * R ..)
@@ -626,21 +636,21 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
 #pragma unroll 1
       for (int t = 0; t < nst; ++t) {
         __syncthreads();
-        const unsigned char* stage = smem + slot * kStageBytes;
+        const unsigned char* stage = smem + slot * Geo<R>::kStageBytes;
         slot = (slot + 1 == kStages) ? 0 : slot + 1;
 #pragma unroll
         for (int blk = 0; blk < SB; ++blk) {
           if (t * SB + blk < it.KB && nr > 0) {   // (a wave past the item's end only keeps the barriers)
             constexpr int kSlots = RANK == 8 ? 2 : 3;
-            const BlockOperands o = read_block<kSlots>(stage, blk, lane, n, wave);
-            contract_block<kSlots>(o, acc, colsum, sconst);
+            const BlockOperands<R> o = read_block<kSlots, R>(stage, blk, lane, n, wave);
+            contract_block<kSlots, R>(o, acc, colsum, sconst);
           }
         }
       }
       // ---- envelope rows: fix-up, accumulate over the modes, store
       __syncthreads();
       {
-        const _Float16* eoh = reinterpret_cast<const _Float16*>(smem + slot * kStageBytes);
+        const _Float16* eoh = reinterpret_cast<const _Float16*>(smem + slot * Geo<R>::kStageBytes);
         slot = (slot + 1 == kStages) ? 0 : slot + 1;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -663,7 +673,7 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
     }
     item += stride;
     if (item >= i_hi) break;
-    it = load_item<BATCH>(items, single, item);
+    it = load_item<BATCH, R>(items, single, item);
   }
 }
 
@@ -827,25 +837,36 @@ __global__ __launch_bounds__(64 * kSplitWaves) void stage_mx_split_kernel(SplitA
 
 static int max_workgroups() { return kWgsPerCu * compute_units(); }
 
-template <bool BATCH, int RANK>
-static int launch_br(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
+template <bool BATCH, int RANK, int R>
+static int launch_brr(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
   static KernelSetup setup;
   if (int e = kernel_setup(setup, [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH, RANK>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH, RANK, R>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, Geo<R>::kSmemBytes);
       }))
     return e;
   const int max_wgs = max_workgroups();
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
-  hipLaunchKernelGGL((stage_mx_kernel<BATCH, RANK>), dim3((unsigned)nwg), dim3(kThreads), kSmemBytes, s, items_dev,
-                     nitems, *single);
+  hipLaunchKernelGGL((stage_mx_kernel<BATCH, RANK, R>), dim3((unsigned)nwg), dim3(kThreads), Geo<R>::kSmemBytes, s,
+                     items_dev, nitems, *single);
   return (int)hipGetLastError();
 }
 
+// item_tiles: row tiles per work item of the launch, 8 R
+template <bool BATCH, int RANK>
+static int launch_br(const WorkItem* items_dev, int nitems, int item_tiles, const StageProb* single, hipStream_t s) {
+  switch (item_tiles) {
+    case 64: return launch_brr<BATCH, RANK, 8>(items_dev, nitems, single, s);
+    case 56: return launch_brr<BATCH, RANK, 7>(items_dev, nitems, single, s);
+    case 48: return launch_brr<BATCH, RANK, 6>(items_dev, nitems, single, s);
+    default: return (int)hipErrorInvalidValue;
+  }
+}
+
 template <bool BATCH>
-static int launch_b(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
-  if (single->l == 8) return launch_br<BATCH, 8>(items_dev, nitems, single, s);
-  return launch_br<BATCH, 16>(items_dev, nitems, single, s);
+static int launch_b(const WorkItem* items_dev, int nitems, int item_tiles, const StageProb* single, hipStream_t s) {
+  if (single->l == 8) return launch_br<BATCH, 8>(items_dev, nitems, item_tiles, single, s);
+  return launch_br<BATCH, 16>(items_dev, nitems, item_tiles, single, s);
 }
 
 }  // namespace mx
@@ -869,22 +890,43 @@ int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, con
 
 size_t xs_bytes_for_mx(int K, int T) { return (size_t)T * (size_t)num_blocks(K) * (size_t)mx::kBlockBytes; }
 
-int mx_item_tiles() { return mx::kItemTiles; }
+int mx_item_tiles() { return mx::kComputeWaves * mx::kMaxR; }
+
+// Row tiles per work item for a launch over problems of ntiles[i] row tiles and kb[i] column blocks: 64, or
+// 56 or 48 where that takes less time by this model: an item costs its blocks times the bytes a block of
+// it moves into LDS (a 5 KB record and 2 KB of sign words per tile row of eight), whatever part of its tile
+// slots is used.  Ties go to the larger item.
+int mx_pick_item_tiles(int count, const int* ntiles, const int* kb) {
+  long best = -1;
+  int best_r = mx::kMaxR;
+  for (int r = mx::kMaxR; r >= 6; --r) {
+    long cost = 0;
+    for (int i = 0; i < count; ++i)
+      cost += (long)((ntiles[i] + mx::kComputeWaves * r - 1) / (mx::kComputeWaves * r)) * kb[i] * (5 + 2 * r);
+    if (best < 0 || cost < best) {
+      best = cost;
+      best_r = r;
+    }
+  }
+  return mx::kComputeWaves * best_r;
+}
 
 int mx_max_workgroups() { return mx::max_workgroups(); }
 
 bool stage_is_mx(const StageProb& p) {
-  // an item's sign words must be addressable with 32-bit offsets from its first tile
+  // the sign words must be addressable with 32-bit offsets from the start of the packed matrix
   return (p.l == 16 || p.l == 8) && p.env_dt == MDBF_F16 && p.KB >= 2 && p.xs != nullptr && p.T <= kMaxPreTokens &&
-         (size_t)kGroupTiles * (size_t)p.KB * 256u < (1ull << 31);
+         packed_words(p.rows, p.K) * 4u < (1ull << 31);
 }
 
 int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
   if (!items_dev) {
-    nitems = (single->ntiles + mx::kItemTiles - 1) / mx::kItemTiles;
-    return mx::launch_b<false>(nullptr, nitems, single, s);
+    const int item_tiles = mx_pick_item_tiles(1, &single->ntiles, &single->KB);
+    nitems = (single->ntiles + item_tiles - 1) / item_tiles;
+    return mx::launch_b<false>(nullptr, nitems, item_tiles, single, s);
   }
-  return mx::launch_b<true>(items_dev, nitems, single, s);
+  // single->ntiles carries the plan's tiles per item of this stage
+  return mx::launch_b<true>(items_dev, nitems, single->ntiles, single, s);
 }
 
 SplitGeom split_geom(int ntiles, int KB) {
