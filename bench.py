@@ -358,6 +358,44 @@ def main():
         extras["mlp_plan_T1"] = time_mlp_plan(1, 300 // q)
         extras["mlp_plan_T16"] = time_mlp_plan(16, 150 // q)
 
+        # (7) the quantizer's projection on the GPU: MSVID_16 of a 4096 x 2656 factor (the shape of U for the
+        #     attention projections), 8 passes; checked on a 512 x 384 matrix by Theorem 1's closed form (error of
+        #     the projection = tail of |Z|'s spectrum, from numpy's SVD)
+        def time_msvid(rows, cols, l, iters, reps):
+            gen = torch.Generator(device="cuda:0")
+            gen.manual_seed(77)
+            Z = torch.randn((rows, cols), generator=gen, device="cuda:0")
+            b = mb.mdbf_msvid_block(l)
+            X0 = torch.randn((cols, b), generator=gen, device="cuda:0")
+            need = mb.C.c_size_t(0)
+            mb.lib().mdbf_msvid_workspace_bytes(rows, cols, l, mb.C.byref(need))
+            wsb = torch.empty(need.value, dtype=torch.uint8, device="cuda:0")
+            fn = lambda: mb.mdbf_msvid(Z, l, X0, iters=iters, workspace=wsb)
+            preheat(torch, fn, min(a.preheat_ms, 50.0))
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            # Z is read once per product (2 per pass + 1 for the Rayleigh-Ritz step) and once, with a transposed
+            # copy and the int8 mask written, at the start
+            nbytes = (2 * iters + 1 + 2) * rows * cols * 4 + rows * cols
+            Zs = synth.normal_block(512, 384, 5).astype(np.float64)
+            S, A, Q, sg = mb.mdbf_msvid(torch.from_numpy(Zs.astype(np.float32)).cuda(), l,
+                                        torch.from_numpy(synth.normal_block(384, b, 6)).cuda(), iters=iters)
+            torch.cuda.synchronize()
+            sig = np.linalg.svd(np.abs(Zs), compute_uv=False)
+            err = np.linalg.norm(Zs - S.cpu().numpy() * (A.cpu().numpy().astype(np.float64) @ Q.cpu().numpy().astype(np.float64).T))
+            return {"rows": rows, "cols": cols, "l": l, "passes": iters, "ms_per_call": ms,
+                    "error_over_optimum_512x384": float(err / np.sqrt((sig[l:] ** 2).sum())),
+                    "mask_exact_512x384": bool((S.cpu().numpy() == np.where(Zs < 0, -1, 1)).all()),
+                    "roofline": {"bound": "hbm", "kernel": "abs_t_mul_kernel", "achieved": nbytes / ms / 1e6,
+                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS,
+                                 "algorithmic_bytes_per_call": nbytes}}
+
+        extras["msvid_4096x2656_l16"] = time_msvid(4096, 2656, 16, 8, 100 // q)
+
     out = {
         "metric": "MDBF decode GEMV HBM GB/s (% peak) + prefill TFLOP/s, LLaMA-7B shapes",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,

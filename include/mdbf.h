@@ -229,6 +229,32 @@ int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t 
  * bytes: positive multiple of 16; sink_words: multiple of 4 in [4, 1 << 20]; pointers 16-byte aligned. */
 int mdbf_stream_read(const void* src_dev, size_t bytes, uint32_t* sink_dev, int sink_words, void* stream);
 
+/* ---- quantizer projection (offline) ----------------------------------------------------------
+ * MSVID_l of a real matrix Z (paper Sec. 4.2, Eq. "msvid-def"): the sign mask S = sign(Z) (sign(0) = +1) and the
+ * best rank-l approximation of |Z| in Frobenius norm, A Q^T = TSVD_l(|Z|), with the singular values split
+ * evenly between A (rows x l) and Q (cols x l); S o (A Q^T) is the member of the format nearest to Z for the
+ * mask S (Theorem 1, Eq. "Ustar"), at a distance of the tail of |Z|'s spectrum (Eq. "rankl-error").  This is
+ * the projection the layer-wise optimisation applies to each factor (Eq. "admm-U-prox"); applied to a factor
+ * U (N x R) it yields S_a, A, Q of the stored format, and to V (M x R) it yields S_b, B, G.
+ * The truncated SVD is a block subspace iteration with b = mdbf_msvid_block(l) columns (l plus 8 to 15 of
+ * oversampling) started from the caller's block X0 (cols x b, row-major, linearly independent columns: e.g.
+ * seeded normal deviates; the library draws no random numbers) and ended by a Rayleigh-Ritz step; `iters`
+ * (0 .. 64) is the number of passes (each is one product with |Z| and one with |Z|^T).  The result is the
+ * exact TSVD_l once the iteration has converged: the error A Q^T leaves exceeds the optimum by a factor that
+ * falls geometrically with iters at the rate of the gap between |Z|'s singular values l and b + 1.
+ *   Z_dev      rows x cols, row-major fp32, leading dimension ld >= cols
+ *   S_dev      rows x cols int8 (+1 / -1), row-major, ld = cols: the input mdbf_pack takes
+ *   A_dev, Q_dev   rows x l and cols x l fp32, row-major;  sigma_dev  b Ritz values (fp32, descending; the first l
+ *              are the singular values of A Q^T)
+ *   workspace_dev  caller-owned, >= mdbf_msvid_workspace_bytes (a transposed copy of Z and the iteration's blocks)
+ * Needs b <= min(rows, cols) (else MDBF_EUNSUPPORTED), 1 <= l <= MDBF_MAX_L, pointers 16-byte aligned.
+ * Asynchronous on `stream`; no host synchronisation, no allocation; deterministic (fixed summation orders). */
+int mdbf_msvid_block(int l);
+int mdbf_msvid_workspace_bytes(int rows, int cols, int l, size_t* bytes_out);
+int mdbf_msvid(const float* Z_dev, int rows, int cols, int64_t ld, int l, int iters, const float* X0_dev,
+               int8_t* S_dev, float* A_dev, float* Q_dev, float* sigma_dev, void* workspace_dev,
+               size_t workspace_bytes, void* stream);
+
 /* ---- misc ----------------------------------------------------------------------------- */
 const char* mdbf_strerror(int status);
 const char* mdbf_last_hip_error(void);   /* text of the last failed HIP call on this thread, or "" */

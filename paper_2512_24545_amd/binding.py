@@ -27,6 +27,7 @@ EXPORTS = [
     "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack", "mdbf_pad_envelope",
     "mdbf_stream_read", "mdbf_workspace_bytes", "mdbf_forward", "mdbf_forward_static", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
     "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_batch_plan_kernel", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
+    "mdbf_msvid_block", "mdbf_msvid_workspace_bytes", "mdbf_msvid",
 ]
 
 
@@ -87,6 +88,10 @@ def lib():
     L.mdbf_forward_batch_part.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
     L.mdbf_batch_plan_kernel.restype = C.c_char_p
     L.mdbf_batch_plan_kernel.argtypes = [C.c_void_p, C.c_size_t, C.c_int]
+    L.mdbf_msvid_block.argtypes = [C.c_int]
+    L.mdbf_msvid_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    L.mdbf_msvid.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.mdbf_strerror.restype = C.c_char_p
     L.mdbf_strerror.argtypes = [C.c_int]
     L.mdbf_last_hip_error.restype = C.c_char_p
@@ -308,3 +313,33 @@ def mdbf_forward_batch(plan, stream=None):
 
 def mdbf_forward_batch_part(plan, stages, kernels, stream=None):
     plan.run_part(stages, kernels, stream)
+
+
+# ---- quantizer projection --------------------------------------------------------------------
+def mdbf_msvid_block(l):
+    b = lib().mdbf_msvid_block(l)
+    if b < 0:
+        raise MdbfError(b, "mdbf_msvid_block")
+    return b
+
+
+def mdbf_msvid(Z, l, X0, iters=8, stream=None, workspace=None):
+    """MSVID_l of the CUDA fp32 matrix Z (rows x cols): returns (S int8 +-1, A rows x l, Q cols x l, sigma b).
+    X0: the start block of the subspace iteration, cols x mdbf_msvid_block(l), fp32, on the device."""
+    torch = _torch()
+    assert Z.is_cuda and Z.dim() == 2 and Z.dtype == torch.float32 and Z.stride(1) == 1
+    rows, cols = Z.shape
+    b = mdbf_msvid_block(l)
+    assert X0.is_cuda and X0.dtype == torch.float32 and tuple(X0.shape) == (cols, b) and X0.is_contiguous()
+    need = C.c_size_t(0)
+    _check(lib().mdbf_msvid_workspace_bytes(rows, cols, l, C.byref(need)), "mdbf_msvid_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=Z.device)
+    S = torch.empty((rows, cols), dtype=torch.int8, device=Z.device)
+    A = torch.empty((rows, l), dtype=torch.float32, device=Z.device)
+    Q = torch.empty((cols, l), dtype=torch.float32, device=Z.device)
+    sigma = torch.empty((b,), dtype=torch.float32, device=Z.device)
+    _check(lib().mdbf_msvid(Z.data_ptr(), rows, cols, Z.stride(0), l, iters, X0.data_ptr(), S.data_ptr(), A.data_ptr(),
+                            Q.data_ptr(), sigma.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                            _stream_ptr(stream)), "mdbf_msvid")
+    return S, A, Q, sigma

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(PKG_DIR, "libmdbf.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
 SOURCES = ["mdbf_api.hip", "mdbf_pack.hip", "mdbf_precise.hip", "mdbf_stage_mfma.hip", "mdbf_stage_mx.hip", "mdbf_stage_gemm.hip",
-           "mdbf_stage_generic.hip"]
+           "mdbf_stage_generic.hip", "mdbf_msvid.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -691,6 +691,41 @@ const char* mdbf_batch_plan_kernel(const void* plan_host, size_t plan_bytes, int
   return "stage_generic_kernel";
 }
 
+int mdbf_msvid_block(int l) {
+  if (l < 1 || l > MDBF_MAX_L) return MDBF_EINVAL;
+  return msvid_block(l);
+}
+
+static int check_msvid_shape(int rows, int cols, int l) {
+  if (rows <= 0 || cols <= 0 || l < 1 || l > MDBF_MAX_L) return MDBF_EINVAL;
+  const int b = msvid_block(l);
+  if (b > rows || b > cols) return MDBF_EUNSUPPORTED;
+  return MDBF_OK;
+}
+
+int mdbf_msvid_workspace_bytes(int rows, int cols, int l, size_t* bytes_out) {
+  if (!bytes_out) return MDBF_EINVAL;
+  int st = check_msvid_shape(rows, cols, l);
+  if (st) return st;
+  *bytes_out = msvid_ws_bytes(rows, cols, l);
+  return MDBF_OK;
+}
+
+int mdbf_msvid(const float* Z_dev, int rows, int cols, int64_t ld, int l, int iters, const float* X0_dev,
+               int8_t* S_dev, float* A_dev, float* Q_dev, float* sigma_dev, void* workspace_dev,
+               size_t workspace_bytes, void* stream) {
+  int st = check_msvid_shape(rows, cols, l);
+  if (st) return st;
+  if (!Z_dev || !X0_dev || !S_dev || !A_dev || !Q_dev || !sigma_dev || !workspace_dev) return MDBF_EINVAL;
+  if (ld < cols || iters < 0 || iters > 64) return MDBF_EINVAL;
+  if (!aligned16(Z_dev) || !aligned16(X0_dev) || !aligned16(S_dev) || !aligned16(A_dev) || !aligned16(Q_dev) ||
+      !aligned16(sigma_dev) || !aligned16(workspace_dev))
+    return MDBF_EALIGN;
+  if (workspace_bytes < msvid_ws_bytes(rows, cols, l)) return MDBF_EWORKSPACE;
+  return hip_fail(launch_msvid(Z_dev, rows, cols, ld, l, iters, X0_dev, S_dev, A_dev, Q_dev, sigma_dev, workspace_dev,
+                               (hipStream_t)stream));
+}
+
 const char* mdbf_strerror(int status) {
   switch (status) {
     case MDBF_OK: return "ok";

@@ -209,6 +209,12 @@ int gemm_plan_max_tokens();
 // gemm_plan_max_tokens() tokens per problem); p->T = the longest token count among its problems, mode as above.
 int launch_stage_gemm(const WorkItem* items_dev, int nitems, int mode, const StageProb* p, hipStream_t s);
 
+// MSVID_l (sign mask + truncated SVD of |Z| by block subspace iteration), csrc/mdbf_msvid.hip
+int msvid_block(int l);                                  // columns of the iteration's block: l plus oversampling
+size_t msvid_ws_bytes(int rows, int cols, int l);
+int launch_msvid(const float* Z, int rows, int cols, int64_t ld, int l, int iters, const float* X0, int8_t* S, float* A,
+                 float* Q, float* sigma, void* ws, hipStream_t s);
+
 // dtype helpers (device)
 __device__ inline float load_as_float(const void* p, int64_t idx, int dt) {
   if (dt == MDBF_F32) return ((const MDBF_GLOBAL float*)p)[idx];

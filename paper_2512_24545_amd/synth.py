@@ -95,6 +95,12 @@ def make_activations(n, T, seed, x_dtype="f16", kind="normal"):
     return round_to_dtype(x, x_dtype)
 
 
+def normal_block(rows, cols, seed):
+    """Seeded N(0,1) block (fp32): the start block of the subspace iteration inside mdbf_msvid, which draws no
+    random numbers itself."""
+    return np.random.default_rng(seed).standard_normal((rows, cols)).astype(np.float32)
+
+
 # ---------------------------------------------------------------------------
 # the benchmark configurations
 # ---------------------------------------------------------------------------

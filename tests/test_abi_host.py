@@ -330,6 +330,27 @@ def test_block_scaled_plan_picks_the_item_size_that_wastes_fewest_tile_slots():
         _covered_once(tables[s], [(4096, 4096, 2656)] * 200 + [(4096, 4096, 4096)] * 200, s)
 
 
+def test_msvid_argument_checks_and_workspace():
+    """mdbf_msvid: block sizes, shape limits and the workspace formula, all on the host."""
+    L = mb.lib()
+    assert [L.mdbf_msvid_block(l) for l in (1, 8, 9, 16)] == [16, 16, 24, 24]
+    assert L.mdbf_msvid_block(0) == -1 and L.mdbf_msvid_block(17) == -1
+    need = C.c_size_t(0)
+    assert L.mdbf_msvid_workspace_bytes(4096, 2656, 16, C.byref(need)) == 0
+    # at least the transposed copy of Z, the partial products of the wider orientation and three blocks
+    b = 24
+    assert need.value >= 4096 * 2656 * 4 + 32 * 2656 * b * 4 + (4096 + 2 * 2656) * b * 4
+    assert need.value < 2 * 4096 * 2656 * 4
+    assert L.mdbf_msvid_workspace_bytes(20, 2656, 16, C.byref(need)) == -5      # fewer rows than block columns
+    assert L.mdbf_msvid_workspace_bytes(4096, 2656, 17, C.byref(need)) == -1
+    call = lambda rows=512, cols=384, ld=384, l=4, iters=8, Z=FAKE, ws=FAKE, wsb=1 << 30: L.mdbf_msvid(
+        Z, rows, cols, ld, l, iters, FAKE, FAKE, FAKE, FAKE, FAKE, ws, wsb, None)
+    assert call(Z=None) == -1 and call(ld=383) == -1 and call(iters=65) == -1 and call(iters=-1) == -1
+    assert call(l=0) == -1 and call(rows=10) == -5
+    assert call(Z=FAKE + 4) == -2 and call(ws=FAKE + 8) == -2
+    assert call(wsb=1024) == -4
+
+
 def test_strerror():
     L = mb.lib()
     assert L.mdbf_strerror(0) == b"ok"
