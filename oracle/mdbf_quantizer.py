@@ -7,7 +7,8 @@ with the HIP library and never calls it.  Plain numpy in float64; `numpy.linalg.
 
 What it is for: the forward kernels are checked on factors with the structure a real quantisation run
 produces (mixed-sign envelope modes of decaying size, sign masks correlated with the weights), next to the
-i.i.d. factors the benchmark configurations prescribe.  There is no HIP quantizer to compare it with.
+i.i.d. factors the benchmark configurations prescribe; and the HIP library's MSVID_l entry point (mdbf_msvid)
+is compared with msvid() and with Theorem 1's closed form in tests/test_gpu_msvid.py.
 
 Notation (paper -> here): W (N x M) ~ U V^T, U = S_a o (A Q^T) (N x R), V = S_b o (B G^T) (M x R).  The
 forward oracle's layer uses m = N, n = M, k = R, SA = S_a, SB = S_b^T, and the same A, Q, G, B.
