@@ -396,6 +396,61 @@ def main():
 
         extras["msvid_4096x2656_l16"] = time_msvid(4096, 2656, 16, 8, 100 // q)
 
+        # (8) the decoder stack at 1.5 bits per weight (224 matrices of the LLaMA-7B shapes, one plan) with 1 and
+        #     8 tokens per matrix, and the toy configuration (256 x 256, k = 128, l = 4, fp32: latency only)
+        import types
+        stack = {}
+        for T in (1, 8):
+            r = workloads.run_stack(torch, types.SimpleNamespace(budget="1.5", tokens=T, warmup=30 // q + 1,
+                                                                 passes=100 // q))
+            stack[T] = r
+        toy, toyX = synth.config_toy()
+        tdl = mb.DeviceLayer.from_host(toy)
+        tX = torch.from_numpy(toyX).cuda()
+        tY = mb.mdbf_forward(tdl, tX, y_dtype="f32")
+        torch.cuda.synchronize()
+        toy_err, _ = oracle_check(torch, mb, tdl, tX, tY)
+        e0.record()
+        for _ in range(200 // q):
+            mb.mdbf_forward(tdl, tX, y_dtype="f32", Y=tY)
+        e1.record()
+        torch.cuda.synchronize()
+        toy_us = e0.elapsed_time(e1) * 1e3 / (200 // q)
+
+        # ---- one typed record per benchmark configuration (the figures above, with their roof)
+        def hbm_roof(gbs_):
+            return {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "achieved": gbs_, "frac": gbs_ / HBM_PEAK_GBS}
+        pre = extras["prefill_T2048_attn"]
+        t16 = extras["decode_T16_mlp_gate"]
+        extras["records"] = [
+            {"config": 1, "workload": "toy 256x256 k=128 l=4 T=1, fp32 in/out, one mdbf_forward call", "us_per_call": toy_us,
+             "max_rel_err_vs_oracle": toy_err, "roofline": None, "note": "launch-bound: 22 KB of operands"},
+            {"config": 2, "workload": "attn decode 4096x4096 k=2656 l=16 T=1, %d layers per plan" % a.copies,
+             "kernel": plan.kernel(1), "ms_per_pass": ms_step, "roofline": hbm_roof(gbs),
+             "max_rel_err_vs_oracle": max(err, err_last)},
+            {"config": 2, "workload": "the same layer, one mdbf_forward call (two launches)", "kernel": "stage_mx_split_kernel",
+             "us_per_call": extras["single_call_stream"]["us_per_call"],
+             "roofline": hbm_roof(bytes_call / extras["single_call_stream"]["us_per_call"] / 1e3)},
+            {"config": 3, "workload": "MLP projections 11008x4096 / 4096x11008 k=4096 l=16 T=1, 96 layers per plan",
+             "kernel": extras["mlp_plan_T1"]["kernel"], "ms_per_pass": extras["mlp_plan_T1"]["ms_per_pass"],
+             "roofline": hbm_roof(extras["mlp_plan_T1"]["GB/s"]),
+             "max_rel_err_vs_oracle": extras["mlp_plan_T1"]["max_rel_err_vs_oracle"]},
+            {"config": 3, "workload": "the same with T=16", "kernel": extras["mlp_plan_T16"]["kernel"],
+             "ms_per_pass": extras["mlp_plan_T16"]["ms_per_pass"], "roofline": hbm_roof(extras["mlp_plan_T16"]["GB/s"]),
+             "max_rel_err_vs_oracle": extras["mlp_plan_T16"]["max_rel_err_vs_oracle"],
+             "note": "the binding roof at 16 tokens is the matrix cores (l-expanded or reconstruct order), not HBM"},
+            {"config": 3, "workload": "gate projection 11008x4096 k=4096 T=16, one mdbf_forward call",
+             "kernel": "stage_gemm_split_kernel", "ms_per_call": t16["ms_per_call"], "roofline": t16["roofline"]},
+            {"config": 4, "workload": "prefill 4096x4096 k=2656 l=16 T=2048, one mdbf_forward call",
+             "kernel": "stage_gemm_kernel", "ms_per_call": pre["ms_per_call"], "tokens_per_s": pre["tokens_per_s"],
+             "dense_equivalent_TFLOPs": pre["dense_equivalent_TFLOPs"], "roofline": pre["roofline"]},
+            {"config": 5, "workload": "decoder stack 1.5 bpw, 224 matrices per plan, T=1", "ms_per_pass": stack[1]["ms_per_pass"],
+             "roofline": hbm_roof(stack[1]["GB/s"])},
+            {"config": 5, "workload": "decoder stack 1.5 bpw, 224 matrices per plan, T=8", "ms_per_pass": stack[8]["ms_per_pass"],
+             "roofline": hbm_roof(stack[8]["GB/s"]),
+             "note": "matrix-core bound (reconstruct-order kernel); HBM fraction for comparison only"},
+        ]
+
     out = {
         "metric": "MDBF decode GEMV HBM GB/s (% peak) + prefill TFLOP/s, LLaMA-7B shapes",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
