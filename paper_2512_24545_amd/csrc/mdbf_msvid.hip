@@ -24,6 +24,8 @@ constexpr int kThreads = 256;
 constexpr int kStrip = 128;           // columns per workgroup of the product kernel: two per lane, 4 waves share the rows
 constexpr int kChunkRows = 128;       // rows per workgroup of the product kernel
 constexpr int kBatchRows = 16;        // rows whose loads a wave issues before their arithmetic
+constexpr int kSmallThreads = 1024;   // the b x b kernels (a thread per matrix entry, b <= 32) and the chunk reduction
+                                      // (few workgroups: many loads in flight in each)
 constexpr int kGramRows = 64;         // rows per workgroup of the reduce + Gram kernel
 
 // ---- S = sign(Z) as int8 (+1 / -1, sign(0) = +1: Sec. 2, Notation) and Zt = Z^T, 64 x 64 tiles through LDS
@@ -60,12 +62,12 @@ __global__ __launch_bounds__(kThreads) void abs_t_mul_kernel(const float* __rest
                                                              const double* __restrict__ Tm, float* __restrict__ P) {
   __shared__ __attribute__((aligned(16))) float xs[kChunkRows][BB];
   __shared__ float red[2 * kStrip * BB];
-  __shared__ double tms[BB * BB];
+  __shared__ float tms[BB * BB];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r0 = blockIdx.y * kChunkRows;
   const int nr = min(kChunkRows, R_ - r0);
   if (Tm) {
-    for (int p = tid; p < BB * BB; p += kThreads) tms[p] = Tm[p];
+    for (int p = tid; p < BB * BB; p += kThreads) tms[p] = (float)Tm[p];
     __syncthreads();
   }
   for (int idx = tid; idx < kChunkRows * BB; idx += kThreads) {
@@ -74,10 +76,10 @@ __global__ __launch_bounds__(kThreads) void abs_t_mul_kernel(const float* __rest
     if (r < nr) {
       const float* xr = X + (size_t)(r0 + r) * BB;
       if (Tm) {
-        double sum = 0.0;
-#pragma unroll
-        for (int i = 0; i < BB; ++i) sum += (double)xr[i] * tms[i * BB + j];
-        v = (float)sum;
+        float sum = 0.f;                               // (the span is what matters here; the last block is
+#pragma unroll                                         //  orthonormalised in fp64 by apply_kernel)
+        for (int i = 0; i < BB; ++i) sum = fmaf(xr[i], tms[i * BB + j], sum);
+        v = sum;
       } else {
         v = xr[j];
       }
@@ -152,14 +154,14 @@ __global__ __launch_bounds__(kThreads) void abs_t_mul_kernel(const float* __rest
 
 // ---- Y = sum over chunks of P (in chunk order), and this workgroup's part of Y^T Y
 template <int BB>
-__global__ __launch_bounds__(kThreads) void reduce_gram_kernel(const float* __restrict__ P, int nchunks, int n,
+__global__ __launch_bounds__(kSmallThreads) void reduce_gram_kernel(const float* __restrict__ P, int nchunks, int n,
                                                                float* __restrict__ Y, float* __restrict__ Gp) {
   __shared__ float ys[kGramRows * BB];
   const int tid = threadIdx.x;
   const int row0 = blockIdx.x * kGramRows;
   const int nrow = min(kGramRows, n - row0);
   const size_t plane = (size_t)n * BB;
-  for (int idx = tid; idx < kGramRows * BB; idx += kThreads) {
+  for (int idx = tid; idx < kGramRows * BB; idx += blockDim.x) {
     float y = 0.f;
     if (idx < nrow * BB) {
       const size_t e = (size_t)row0 * BB + idx;
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(kThreads) void reduce_gram_kernel(const float* __re
     ys[idx] = y;
   }
   __syncthreads();
-  for (int p = tid; p < BB * BB; p += kThreads) {
+  for (int p = tid; p < BB * BB; p += blockDim.x) {
     const int i = p / BB, j = p - i * BB;
     float g = 0.f;
     for (int r = 0; r < kGramRows; ++r) g = fmaf(ys[r * BB + i], ys[r * BB + j], g);
@@ -189,12 +191,12 @@ template <int BB>
 __device__ void gather_gram(const float* __restrict__ Gp, int nparts, double (&G)[BB][BB]) {
   for (int p = threadIdx.x; p < BB * BB; p += blockDim.x) {
     double sum = 0.0;
-    for (int w0 = 0; w0 < nparts; w0 += 8) {
-      float v[8];
+    for (int w0 = 0; w0 < nparts; w0 += 16) {       // sixteen loads in flight, added in part order
+      float v[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = Gp[(size_t)min(w0 + u, nparts - 1) * BB * BB + p];
+      for (int u = 0; u < 16; ++u) v[u] = Gp[(size_t)min(w0 + u, nparts - 1) * BB * BB + p];
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < 16; ++u)
         if (w0 + u < nparts) sum += (double)v[u];
     }
     G[p / BB][p % BB] = sum;
@@ -202,55 +204,64 @@ __device__ void gather_gram(const float* __restrict__ Gp, int nparts, double (&G
   __syncthreads();
 }
 
-// ---- Cholesky-QR: G = R^T R (R upper triangular), Tm = R^(-1): Y Tm has orthonormal columns.  One workgroup.
+// a double held by lane `src` (a compile-time or wave-uniform index), in every lane
+__device__ __forceinline__ double lane_value(double v, int src) {
+  const uint64_t u = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, src);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), src);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// ---- Cholesky-QR: G = R^T R (R upper triangular), Tm = R^(-1): Y Tm has orthonormal columns.
+// The whole workgroup adds up the Gram parts; the factorisation itself runs in one wave, lane j holding column j
+// of the matrix in registers (right-looking: after step k the trailing columns hold the Schur complement), with
+// row k passed round by lane reads: no LDS traffic and no barrier inside the b steps.
+// A column that the earlier ones span (|Z| of lower rank than the block is wide: a member of the format is) has
+// a pivot at the level of the Gram matrix's rounding, 1e-6 of its diagonal entry (fp32 partial sums): such a
+// column is dropped (its column of Tm is zero, and stays zero through the products that follow).
 template <int BB>
-__global__ __launch_bounds__(kThreads) void chol_kernel(const float* __restrict__ Gp, int nparts, double* __restrict__ Tm) {
+__global__ __launch_bounds__(kSmallThreads) void chol_kernel(const float* __restrict__ Gp, int nparts, double* __restrict__ Tm) {
   __shared__ double G[BB][BB];
-  __shared__ double Rm[BB][BB];
-  __shared__ double Ri[BB][BB];
-  const int t = threadIdx.x;
   gather_gram<BB>(Gp, nparts, G);
-  __shared__ int dead[BB];
-  for (int p = t; p < BB * BB; p += blockDim.x) { Rm[p / BB][p % BB] = 0.0; Ri[p / BB][p % BB] = 0.0; }
-  __syncthreads();
-  // R row by row: R[k][k] = sqrt(G[k][k] - sum_{i<k} R[i][k]^2),  R[k][j] = (G[k][j] - sum_{i<k} R[i][k] R[i][j]) / R[k][k].
-  // A column that the earlier ones span (|Z| of lower rank than the block is wide: a member of the format is) has
-  // a pivot at the level of the Gram matrix's rounding, 1e-6 of its diagonal entry (fp32 partial sums): such a
-  // column is dropped (its column of Tm is zero, and stays zero through the products that follow).
+  if (threadIdx.x >= 64) return;                       // (no barrier below)
+  const int j = (int)threadIdx.x;
+  const int jc = min(j, BB - 1);                       // lanes past the last column shadow it and store nothing
+  double a[BB], rk[BB], rinv[BB];
+  uint32_t dead = 0;
+#pragma unroll
+  for (int i = 0; i < BB; ++i) a[i] = G[i][jc];
+#pragma unroll
   for (int k = 0; k < BB; ++k) {
-    if (t >= k && t < BB) {
-      double sum = G[k][t];
-      for (int i = 0; i < k; ++i) sum -= Rm[i][k] * Rm[i][t];
-      Rm[k][t] = sum;             // not yet divided
-    }
-    __syncthreads();
-    const double piv = Rm[k][k];
-    const bool drop = !(piv > 1e-6 * G[k][k]) || !(G[k][k] > 0.0);
-    const double d = drop ? 1.0 : sqrt(piv);
-    __syncthreads();
-    if (t >= k && t < BB) Rm[k][t] = (t == k) ? d : (drop ? 0.0 : Rm[k][t] / d);
-    if (t == 0) dead[k] = drop ? 1 : 0;
-    __syncthreads();
+    const double piv = lane_value(a[k], k);            // the Schur complement's diagonal entry
+    const double g0 = G[k][k];
+    const bool drop = !(piv > 1e-6 * g0) || !(g0 > 0.0);
+    const double rd = drop ? 1.0 : 1.0 / sqrt(piv);
+    rinv[k] = rd;
+    dead |= drop ? (1u << k) : 0u;
+    rk[k] = (jc < k) ? 0.0 : (jc == k) ? (drop ? 1.0 : piv * rd) : (drop ? 0.0 : a[k] * rd);   // R[k][jc]
+#pragma unroll
+    for (int i = k + 1; i < BB; ++i) a[i] -= lane_value(rk[k], i) * rk[k];
   }
-  // inverse of the upper-triangular R, column j by thread j (back substitution on R X = I)
-  if (t < BB) {
-    const int j = t;
-    for (int i = j; i >= 0; --i) {
-      double sum = (i == j) ? 1.0 : 0.0;
-      for (int m = i + 1; m <= j; ++m) sum -= Rm[i][m] * Ri[m][j];
-      Ri[i][j] = sum / Rm[i][i];
-    }
-    if (dead[j])
-      for (int i = 0; i <= j; ++i) Ri[i][j] = 0.0;
+  // column jc of R^(-1) by back substitution on R X = I (entries below the diagonal come out zero)
+  double x[BB];
+#pragma unroll
+  for (int i = BB - 1; i >= 0; --i) {
+    double sum = (i == jc) ? 1.0 : 0.0;
+#pragma unroll
+    for (int m = i + 1; m < BB; ++m) sum -= lane_value(rk[i], m) * x[m];
+    x[i] = sum * rinv[i];
   }
-  __syncthreads();
-  for (int p = t; p < BB * BB; p += blockDim.x) Tm[p] = Ri[p / BB][p % BB];
+  if (j < BB) {
+    const bool gone = (dead >> j) & 1u;
+#pragma unroll
+    for (int i = 0; i < BB; ++i) Tm[i * BB + j] = gone ? 0.0 : x[i];
+  }
 }
 
 // ---- Rayleigh-Ritz: G = B^T B = W L W^T by cyclic Jacobi in fp64; Ritz values sigma_i = sqrt(L_i), descending.
 // MA = W_l Sigma_l^(-1/2) (A = B MA), MQ = W_l Sigma_l^(1/2) (Q = V MQ); both BB x BB row-major, columns >= l zero.
 template <int BB>
-__global__ __launch_bounds__(kThreads) void ritz_kernel(const float* __restrict__ Gp, int nparts, int l,
+__global__ __launch_bounds__(kSmallThreads) void ritz_kernel(const float* __restrict__ Gp, int nparts, int l,
                                                   double* __restrict__ MA, double* __restrict__ MQ,
                                                   float* __restrict__ sigma) {
   __shared__ double a[BB][BB];
@@ -392,16 +403,16 @@ static int run(const float* Z, int rows, int cols, int64_t ld, int l, int iters,
     const int nchunks = (R_ + kChunkRows - 1) / kChunkRows;
     hipLaunchKernelGGL(abs_t_mul_kernel<BB>, dim3((C_ + kStrip - 1) / kStrip, nchunks), blk, 0, s, Mx, R_, C_, ldm, X, Tx, P);
     const int nparts = (C_ + kGramRows - 1) / kGramRows;
-    hipLaunchKernelGGL(reduce_gram_kernel<BB>, dim3(nparts), blk, 0, s, P, nchunks, C_, Y, Gp);
+    hipLaunchKernelGGL(reduce_gram_kernel<BB>, dim3(nparts), dim3(kSmallThreads), 0, s, P, nchunks, C_, Y, Gp);
     return nparts;
   };
   const float* X = X0;
   const double* Tx = nullptr;
   for (int it = 0; it < iters; ++it) {
     int np = product(Zt, cols, rows, rows, X, Tx, Yb);                 // B = |Z| V
-    hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), blk, 0, s, Gp, np, Tm);
+    hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), dim3(kSmallThreads), 0, s, Gp, np, Tm);
     np = product(Z, rows, cols, ld, Yb, Tm, Yc);                       // V = |Z|^T B
-    hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), blk, 0, s, Gp, np, Tm);
+    hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), dim3(kSmallThreads), 0, s, Gp, np, Tm);
     X = Yc;
     Tx = Tm;
   }
@@ -409,16 +420,16 @@ static int run(const float* Z, int rows, int cols, int64_t ld, int l, int iters,
   const int grid_apply = 1024;
   const int npc = (cols + kGramRows - 1) / kGramRows;
   if (iters == 0) {
-    hipLaunchKernelGGL(reduce_gram_kernel<BB>, dim3(npc), blk, 0, s, X0, 1, cols, Yc, Gp);
-    hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), blk, 0, s, Gp, npc, Tm);
+    hipLaunchKernelGGL(reduce_gram_kernel<BB>, dim3(npc), dim3(kSmallThreads), 0, s, X0, 1, cols, Yc, Gp);
+    hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), dim3(kSmallThreads), 0, s, Gp, npc, Tm);
   }
   hipLaunchKernelGGL(apply_kernel<BB>, dim3(grid_apply), blk, 0, s, Yc, cols, Tm, BB, V1);
-  hipLaunchKernelGGL(reduce_gram_kernel<BB>, dim3(npc), blk, 0, s, V1, 1, cols, Yc, Gp);   // (Yc = copy of V1)
-  hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), blk, 0, s, Gp, npc, Tm);
+  hipLaunchKernelGGL(reduce_gram_kernel<BB>, dim3(npc), dim3(kSmallThreads), 0, s, V1, 1, cols, Yc, Gp);   // (Yc = copy of V1)
+  hipLaunchKernelGGL(chol_kernel<BB>, dim3(1), dim3(kSmallThreads), 0, s, Gp, npc, Tm);
   hipLaunchKernelGGL(apply_kernel<BB>, dim3(grid_apply), blk, 0, s, Yc, cols, Tm, BB, V1);        // V1 = V, orthonormal
   // Rayleigh-Ritz on B = |Z| V
   const int npb = product(Zt, cols, rows, rows, V1, nullptr, Yb);
-  hipLaunchKernelGGL(ritz_kernel<BB>, dim3(1), blk, 0, s, Gp, npb, l, MA, MQ, sigma);
+  hipLaunchKernelGGL(ritz_kernel<BB>, dim3(1), dim3(kSmallThreads), 0, s, Gp, npb, l, MA, MQ, sigma);
   hipLaunchKernelGGL(apply_kernel<BB>, dim3(grid_apply), blk, 0, s, Yb, rows, MA, l, A);
   hipLaunchKernelGGL(apply_kernel<BB>, dim3(grid_apply), blk, 0, s, V1, cols, MQ, l, Q);
   return (int)hipGetLastError();
