@@ -212,7 +212,10 @@ def main():
         plan.run_part(3, 1)
     e1.record()
     torch.cuda.synchronize()
-    avg_scale_in_ms = e0.elapsed_time(e1) / (2 * part_steps)
+    # scale-in launches per step: two, or one when the first factor's product launch writes the second factor's
+    # activation records itself (three launches per step)
+    n_si = max(plan.launches() - 2, 1)
+    avg_scale_in_ms = e0.elapsed_time(e1) / (n_si * part_steps)
     traffic = None   # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE runs
     tpath = os.path.join(ROOT, "profiles", "traffic_attn_decode.json")
     if os.path.exists(tpath):
@@ -223,11 +226,13 @@ def main():
     # the share of a layer's algorithmic bytes that the product kernel itself moves, averaged over its two
     # launches per step: the packed signs of the factor, the envelope factor on its output side (G resp. A)
     # and y; the other envelope factor (B resp. Q) and x are read by the scale-in kernel
-    product_bytes_layer = ((M + N) * K // 8 + 2 * L * (K + M) + 2 * M) / 2
-    scale_in_bytes_layer = (2 * L * (N + K) + 2 * N) / 2
-    assert 2 * (product_bytes_layer + scale_in_bytes_layer) == algorithmic_bytes(M, N, K, L)
+    q_in_product = 2 * L * K if n_si == 1 else 0     # the envelope factor Q: read by whoever builds the z records
+    product_bytes_layer = ((M + N) * K // 8 + 2 * L * (K + M) + 2 * M + q_in_product) / 2
+    scale_in_bytes_layer = (2 * L * (N + K) + 2 * N - q_in_product) / n_si
+    assert 2 * product_bytes_layer + n_si * scale_in_bytes_layer == algorithmic_bytes(M, N, K, L)
     bytes_launch = product_bytes_layer * a.copies
-    roof = {"bound": "hbm", "kernel": plan.kernel(1), "launches_timed": 2 * part_steps, "achieved": bytes_launch / avg_launch_ms / 1e6,
+    roof = {"bound": "hbm", "kernel": plan.kernel(1), "launches_timed": 2 * part_steps,
+            "launches_per_step": plan.launches(), "achieved": bytes_launch / avg_launch_ms / 1e6,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": traffic,
             "avg_launch_us": avg_launch_ms * 1e3, "algorithmic_bytes_per_launch": bytes_launch,
             "scale_in_avg_launch_us": avg_scale_in_ms * 1e3,

@@ -212,9 +212,16 @@ int mdbf_forward_batch(const void* plan_host, const void* plan_dev, size_t plan_
  * static.  For reports that must name the kernel they timed. */
 const char* mdbf_batch_plan_kernel(const void* plan_host, size_t plan_bytes, int stage);
 
+/* Kernel launches one mdbf_forward_batch of the plan issues (host only): 4 for the block-scaled and fp16-staged
+ * kernels with a scale-in launch per factor, 3 when both factors run the block-scaled kernel (the first factor's
+ * launch writes the second factor's activation records itself), 2 for the others; a negative status for an
+ * invalid plan. */
+int mdbf_batch_plan_launches(const void* plan_host, size_t plan_bytes);
+
 /* Runs a part of a plan, for measuring its kernels one by one: `stages` and `kernels` are bit masks.
  * stages: 1 = first factor (x -> z), 2 = second factor (z -> y).  kernels: 1 = the scale-in kernel of the
- * stage (plans that have none skip it), 2 = the product kernel.  mdbf_forward_batch is (3, 3).  Results are
+ * stage (plans that have none skip it: also the second factor of a three-launch plan, whose records the first
+ * factor's product kernel writes), 2 = the product kernel.  mdbf_forward_batch is (3, 3).  Results are
  * only meaningful if the caller preserves the order scale-in -> product, stage 1 -> stage 2. */
 int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t plan_bytes, int stages,
                             int kernels, void* stream);

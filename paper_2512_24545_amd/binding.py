@@ -26,7 +26,7 @@ STATUS = {0: "MDBF_OK", -1: "MDBF_EINVAL", -2: "MDBF_EALIGN", -3: "MDBF_EDTYPE",
 EXPORTS = [
     "mdbf_bpw", "mdbf_rank_for_budget", "mdbf_packed_bytes", "mdbf_pack", "mdbf_unpack", "mdbf_pad_envelope",
     "mdbf_stream_read", "mdbf_workspace_bytes", "mdbf_forward", "mdbf_forward_static", "mdbf_batch_plan_bytes", "mdbf_batch_plan_build",
-    "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_batch_plan_kernel", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
+    "mdbf_forward_batch", "mdbf_forward_batch_part", "mdbf_batch_plan_kernel", "mdbf_batch_plan_launches", "mdbf_strerror", "mdbf_last_hip_error", "mdbf_version",
     "mdbf_msvid_block", "mdbf_msvid_workspace_bytes", "mdbf_msvid",
 ]
 
@@ -86,6 +86,7 @@ def lib():
     L.mdbf_batch_plan_build.argtypes = [C.c_int, C.POINTER(Layer), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]
     L.mdbf_forward_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.mdbf_forward_batch_part.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
+    L.mdbf_batch_plan_launches.argtypes = [C.c_void_p, C.c_size_t]
     L.mdbf_batch_plan_kernel.restype = C.c_char_p
     L.mdbf_batch_plan_kernel.argtypes = [C.c_void_p, C.c_size_t, C.c_int]
     L.mdbf_msvid_block.argtypes = [C.c_int]
@@ -300,6 +301,10 @@ class BatchPlan:
     def kernel(self, stage):
         """Name of the product kernel the plan runs for stage 1 or 2."""
         return lib().mdbf_batch_plan_kernel(self.plan_host.data_ptr(), self.plan_bytes, stage).decode()
+
+    def launches(self):
+        """Kernel launches one run() issues."""
+        return lib().mdbf_batch_plan_launches(self.plan_host.data_ptr(), self.plan_bytes)
 
     def run_part(self, stages, kernels, stream=None):
         """One part of the plan (bit masks: stages 1|2, kernels 1 = scale-in, 2 = product)."""

@@ -287,7 +287,7 @@ int mdbf_forward(const mdbf_desc_t* desc, const void* SA_packed_dev, const void*
       // element-wise kernel)
       e = launch_scale_in_mx(nullptr, 1, T * sp[i].KB, &sp[i], s);
       if (e) return hip_fail(e);
-      e = launch_stage_mx(nullptr, 0, &sp[i], s);
+      e = launch_stage_mx(nullptr, 0, &sp[i], nullptr, s);
     }
     else if (stage_is_fast(sp[i])) {
       const bool pre = sp[i].xs != nullptr;
@@ -496,6 +496,7 @@ static int batch_layout(int count, const mdbf_layer_t* layers, PlanHeader* h, si
     }
     h->tiles_per_item[s] = h->gemm ? gemm_tiles_per_item() : mx[s] ? tpi_mx : tpi_fp16;
   }
+  h->fuse2 = (!precise && !h->gemm && h->mx[0] != 0 && h->mx[0] == h->mx[1]) ? 1 : 0;
   for (int i = 0; i < count; ++i) {
     nitems[0] += (num_tiles(layers[i].desc.k) + h->tiles_per_item[0] - 1) / h->tiles_per_item[0];
     nitems[1] += (num_tiles(layers[i].desc.m) + h->tiles_per_item[1] - 1) / h->tiles_per_item[1];
@@ -663,9 +664,11 @@ int mdbf_forward_batch_part(const void* plan_host, const void* plan_dev, size_t 
       if (main_k) e = launch_stage_precise(probs, items, h.nitems[st], &dummy, s);
     } else if (h.mx[st]) {
       dummy.l = h.mx[st];
-      if (pre_k) e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
+      // (fused plans: the first stage's product launch has written this stage's records)
+      if (pre_k && !(st == 1 && h.fuse2)) e = launch_scale_in_mx(probs, h.count, h.max_units_mx[st], &dummy, s);
       if (e) return hip_fail(e);
-      if (main_k) e = launch_stage_mx(items, h.nitems[st], &dummy, s);
+      const StageProb* next = (st == 0 && h.fuse2) ? (const StageProb*)(dev + h.probs_off[1]) : nullptr;
+      if (main_k) e = launch_stage_mx(items, h.nitems[st], &dummy, next, s);
     } else if (h.fast[st]) {
       if (h.pre[st] && pre_k) e = launch_scale_in(probs, h.count, h.max_units[st], &dummy, s);
       if (e) return hip_fail(e);
@@ -689,6 +692,22 @@ const char* mdbf_batch_plan_kernel(const void* plan_host, size_t plan_bytes, int
   if (h.mx[st]) return "stage_mx_kernel";
   if (h.fast[st]) return "stage_fast_kernel";
   return "stage_generic_kernel";
+}
+
+int mdbf_batch_plan_launches(const void* plan_host, size_t plan_bytes) {
+  if (!plan_host || plan_bytes < sizeof(PlanHeader)) return MDBF_EINVAL;
+  PlanHeader h;
+  memcpy(&h, plan_host, sizeof(h));
+  if (h.magic != kPlanMagic || h.count < 1) return MDBF_EINVAL;
+  if (h.gemm) return h.max_tokens > gemm_plan_max_tokens() ? 2 * h.count : 2;
+  if (h.precise) return 2;
+  int n = 0;
+  for (int st = 0; st < 2; ++st) {
+    if (h.mx[st]) n += (st == 1 && h.fuse2) ? 1 : 2;
+    else if (h.fast[st]) n += h.pre[st] ? 2 : 1;
+    else n += 1;
+  }
+  return n;
 }
 
 int mdbf_msvid_block(int l) {

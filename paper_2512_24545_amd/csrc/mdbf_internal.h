@@ -114,6 +114,9 @@ struct PlanHeader {
   uint64_t probs_off[2];      // byte offsets of StageProb[count] for stage 1 / 2
   uint64_t items_off[2];      // byte offsets of WorkItem[nitems[s]]
   uint64_t total_bytes;
+  int32_t fuse2;              // both stages run the block-scaled variant at one rank: the first stage's launch
+                              // writes the second stage's activation records (no scale-in launch for stage 2)
+  int32_t pad_;
 };
 constexpr uint32_t kPlanMagic = 0x4D444246u;  // "MDBF"
 
@@ -165,7 +168,11 @@ int launch_scale_in_mx(const StageProb* probs_dev, int count, int max_units, con
 // items_dev null: one problem (`single`), items are cut on the fly
 // single->l = the envelope rank of the launch (16 or 8; a plan's problems all have the same); with items_dev,
 // single->ntiles = the row tiles per work item the plan was cut with (mx_pick_item_tiles)
-int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s);
+// next_probs_dev (plans only, or null): the problems of the factor that follows, indexed like this launch's
+// (WorkItem::prob); with it the launch writes that factor's activation records itself (no scale-in launch
+// for it) and does not store its own results.  Needs that factor to be served by this variant too.
+int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, const StageProb* next_probs_dev,
+                    hipStream_t s);
 // Split variant of the block-scaled kernel for one small problem with one token: workgroup (g, s) takes row
 // tiles 8g .. 8g + 7 and `bs` blocks of the contraction dimension and builds its activation records itself;
 // the partial sums of the nsplit workgroups of a tile group are added in a fixed order, by the reader

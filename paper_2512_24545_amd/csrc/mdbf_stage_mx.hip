@@ -68,6 +68,7 @@ struct Geo {
   static constexpr int kSignInstr = kStageSigns / 1024;
   static constexpr int kEoInstr = kEoBytes / 1024;
   static constexpr int kSmemBytes = kStages * kStageBytes;
+  static constexpr int kZBytes = kItemTiles * kTileRows * 4;      // fused launches: the item's results, behind the ring
   static constexpr int kSignInstrPerBlock = kItemTiles / 4 / kLoaderWaves;   // per loader wave
   static_assert(kItemTiles % 4 == 0, "a loader instruction carries four whole tiles");
   static_assert(kEoBytes <= kStageBytes, "the envelope rows travel in a stage of their own");
@@ -175,45 +176,12 @@ __device__ __forceinline__ void record_store(unsigned char* base, int index, V v
   else __builtin_nontemporal_store(v, &((MDBF_GLOBAL V*)base)[index]);
 }
 
-// the record of block q of the problem's contraction dimension, from the inputs `in`, written to `blk`
+// A lane's 32 values of a block in operand order (val, divided by their nibble values; m = their largest
+// magnitude) -> block exponent, three fp6 limbs, the record's slots, scales and column sums at `blk`.
 template <bool RANK8, bool TO_LDS>
-__device__ __forceinline__ void prep_record_to(const StageProb& p, int q, int lane, const PrepInput& in, float* pr,
-                                               unsigned char* blk) {
-  const int kg = lane >> 4, n = lane & 15;
-  const bool has_modes = (lane & 1) < (p.l >> 3);
-
-  // ---- 1. products
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const bool live = (q * kBlockCols + (lane >> 1) + 32 * i < p.K) && has_modes;
-    const float xk = (p.vin_dt == MDBF_F32)   ? __builtin_bit_cast(float, in.xbits[i])
-                     : (p.vin_dt == MDBF_F16) ? (float)__builtin_bit_cast(_Float16, (uint16_t)in.xbits[i])
-                                              : __builtin_bit_cast(float, in.xbits[i] << 16);
-    const uint32_t w[4] = {in.raw[i].x, in.raw[i].y, in.raw[i].z, in.raw[i].w};
-    float* dst = pr + ((lane >> 1) + 32 * i) * kProdStride + (lane & 1) * 8;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const float lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] & 0xFFFFu));
-      const float hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] >> 16));
-      dst[2 * t] = live ? lo * xk : 0.f;
-      dst[2 * t + 1] = live ? hi * xk : 0.f;
-    }
-  }
-  wave_lds_sync();
-
-  // ---- 2. gather in operand order, quantise.  Rank 8: lanes n and n + 8 both take mode n; the first
-  //         keeps limbs 1 and 3, the second limb 2, so that two matrix-core instructions cover three limbs
+__device__ __forceinline__ void quantise_store(const float (&val)[32], float m, int lane, unsigned char* blk) {
   constexpr bool rank8 = RANK8;   // the launch's rank: every problem of it has l = 8, or every one l = 16
-  const int nsrc = rank8 ? (n & 7) : n;
-  float val[32];
-  float m = 0.f;
-#pragma unroll
-  for (int j = 0; j < 32; ++j) {
-    const float presc = (j < 8) ? 2.f : (j < 16 ? 1.f : (j < 24 ? 0.5f : -0.5f));   // undo the nibble values 0.5, 1, 2, -2
-    val[j] = pr[(local_col_of_element(j, 0) + 8 * kg) * kProdStride + nsrc] * presc;
-    m = fmaxf(m, fabsf(val[j]));
-  }
-  wave_lds_sync();   // the next record's products may overwrite the buffer
+  const int n = lane & 15;
   int E = -100;
   if (m > 0.f) {
     int ex;
@@ -274,6 +242,48 @@ __device__ __forceinline__ void prep_record_to(const StageProb& p, int q, int la
   part += __shfl_xor(part, 16);
   part += __shfl_xor(part, 32);
   if (lane < 16) record_store<TO_LDS>(blk + kColsumOff, lane, part);
+}
+
+
+// the record of block q of the problem's contraction dimension, from the inputs `in`, written to `blk`
+template <bool RANK8, bool TO_LDS>
+__device__ __forceinline__ void prep_record_to(const StageProb& p, int q, int lane, const PrepInput& in, float* pr,
+                                               unsigned char* blk) {
+  const int kg = lane >> 4, n = lane & 15;
+  const bool has_modes = (lane & 1) < (p.l >> 3);
+
+  // ---- 1. products
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool live = (q * kBlockCols + (lane >> 1) + 32 * i < p.K) && has_modes;
+    const float xk = (p.vin_dt == MDBF_F32)   ? __builtin_bit_cast(float, in.xbits[i])
+                     : (p.vin_dt == MDBF_F16) ? (float)__builtin_bit_cast(_Float16, (uint16_t)in.xbits[i])
+                                              : __builtin_bit_cast(float, in.xbits[i] << 16);
+    const uint32_t w[4] = {in.raw[i].x, in.raw[i].y, in.raw[i].z, in.raw[i].w};
+    float* dst = pr + ((lane >> 1) + 32 * i) * kProdStride + (lane & 1) * 8;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] & 0xFFFFu));
+      const float hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] >> 16));
+      dst[2 * t] = live ? lo * xk : 0.f;
+      dst[2 * t + 1] = live ? hi * xk : 0.f;
+    }
+  }
+  wave_lds_sync();
+
+  // ---- 2. gather in operand order, quantise.  Rank 8: lanes n and n + 8 both take mode n; the first
+  //         keeps limbs 1 and 3, the second limb 2, so that two matrix-core instructions cover three limbs
+  const int nsrc = RANK8 ? (n & 7) : n;
+  float val[32];
+  float m = 0.f;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    const float presc = (j < 8) ? 2.f : (j < 16 ? 1.f : (j < 24 ? 0.5f : -0.5f));   // undo the nibble values 0.5, 1, 2, -2
+    val[j] = pr[(local_col_of_element(j, 0) + 8 * kg) * kProdStride + nsrc] * presc;
+    m = fmaxf(m, fabsf(val[j]));
+  }
+  wave_lds_sync();   // the next record's products may overwrite the buffer
+  quantise_store<RANK8, TO_LDS>(val, m, lane, blk);
 }
 
 // record of unit (token, block) of the problem's activation stream in global memory
@@ -357,13 +367,28 @@ struct ItemInfo {
   int64_t out_ld;
   int rows, KB, T, out_dt, flags;
   int tile0, ntl;
+  // fused launches only: the next factor's input-side envelope rows (one per row of this problem), its
+  // activation stream (written here) and its block count
+  const unsigned char* Enext;
+  unsigned char* xs_next;
+  int KB_next;
 };
 
-template <bool BATCH, int R>
-__device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items, const StageProb& single, int item) {
+template <bool BATCH, int R, bool FUSE>
+__device__ __forceinline__ ItemInfo load_item(const WorkItem* __restrict__ items, const StageProb& single, int item,
+                                              const StageProb* __restrict__ next_probs) {
   ItemInfo it;
+  it.Enext = nullptr;
+  it.xs_next = nullptr;
+  it.KB_next = 0;
   if (BATCH) {
     const WorkItem& w = items[item];   // uniform address: scalar loads
+    if (FUSE) {
+      const StageProb& nx = next_probs[w.prob];
+      it.Enext = (const unsigned char*)nx.Ein;
+      it.xs_next = (unsigned char*)nx.xs;
+      it.KB_next = nx.KB;
+    }
     it.S = (const unsigned char*)w.p.S;
     it.xs = (const unsigned char*)w.p.xs;
     it.Eout = (const unsigned char*)w.p.Eout;
@@ -456,14 +481,14 @@ __device__ __forceinline__ void issue_stage(const ItemInfo& it, int b, int q0, u
 // loader: the item's envelope rows (RANK modes of fp16: 32 or 16 bytes per row, rows back to back) into
 // `stage`.  With 16-byte rows the second half of the instructions repeats the last row past the item's end.
 template <int RANK, int LW, int R>
-__device__ __forceinline__ void issue_eo(const ItemInfo& it, unsigned char* stage, int lane) {
+__device__ __forceinline__ void issue_eo(const ItemInfo& it, const unsigned char* rows_base, unsigned char* stage, int lane) {
   constexpr int hsh = RANK >> 4;                // log2 of the 16-byte pieces per row: 1 or 0
 #pragma unroll
   for (int j = 0; j < Geo<R>::kEoInstr / kLoaderWaves; ++j) {
     const int i = j * kLoaderWaves + LW;
     const int piece = 64 * i + lane;
     const int row = min(it.tile0 * kTileRows + (piece >> hsh), it.rows - 1);
-    dma16<true>(it.Eout, ((uint32_t)row << (4 + hsh)) + (uint32_t)(piece & hsh) * 16u, stage + i * 1024);
+    dma16<true>(rows_base, ((uint32_t)row << (4 + hsh)) + (uint32_t)(piece & hsh) * 16u, stage + i * 1024);
   }
 }
 
@@ -520,12 +545,13 @@ __device__ __forceinline__ void contract_block(const BlockOperands<R>& o, floatx
 // every token, ceil(KB / SB) contraction stages followed by one stage with the envelope rows; stage g lives
 // in ring slot g % kStages), two stages ahead of the contraction waves.  Barrier g opens stage g for them
 // and tells the loader that stage g - 1 has been drained, so that its slot can take stage g + 2.
-template <bool BATCH, int RANK, int LW, int R>
+template <bool BATCH, int RANK, int LW, int R, bool FUSE>
 __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, const StageProb& single, int item0,
-                                            int i_hi, int stride, unsigned char* smem, int lane) {
+                                            int i_hi, int stride, unsigned char* smem, int lane,
+                                            const StageProb* __restrict__ next_probs) {
   typedef Geo<R> G;
   int item = item0;
-  ItemInfo it = load_item<BATCH, R>(items, single, item);
+  ItemInfo it = load_item<BATCH, R, FUSE>(items, single, item, next_probs);
   uint32_t voff[R], bstride[R];
   sign_lane_offsets<LW, R>(it, lane, voff, bstride);
   int b = 0, t = 0;                       // cursor: next stage to issue = stage t of (item, b)
@@ -539,12 +565,13 @@ __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, 
       issue_stage<LW, R>(it, b, t * SB, stage, lane, voff, bstride);
       kind_prev = 0;
     } else {
-      issue_eo<RANK, LW, R>(it, stage, lane);
+      // the output side's envelope rows, then (fused launches) the next factor's input-side rows
+      issue_eo<RANK, LW, R>(it, t == nst ? it.Eout : it.Enext, stage, lane);
       kind_prev = 1;
     }
     slot = (slot + 1 == kStages) ? 0 : slot + 1;
     // advance the cursor
-    if (t < nst) {
+    if (t < nst + (FUSE ? 1 : 0)) {
       ++t;
     } else {
       t = 0;
@@ -554,7 +581,7 @@ __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, 
         b = 0;
         item += stride;
         if (item < i_hi) {
-          it = load_item<BATCH, R>(items, single, item);
+          it = load_item<BATCH, R, FUSE>(items, single, item, next_probs);
           sign_lane_offsets<LW, R>(it, lane, voff, bstride);
           nst = (it.KB + SB - 1) / SB;
         } else {
@@ -589,9 +616,17 @@ __device__ __forceinline__ void loader_role(const WorkItem* __restrict__ items, 
 // either way; with rank 8, column n < 8 carries limbs 1 and 3 of mode n and column n + 8 limb 2 of the same
 // mode (each column has its own scales), so a tile and block take two instructions instead of three; the
 // sum over the 16 columns in the epilogue, with mode n's envelope entry on both of its columns, joins them.
-template <bool BATCH, int RANK, int R>
+// FUSE (plans whose next factor runs this kernel too): the launch also writes the next factor's activation
+// records, so that factor needs no scale-in launch and the result of this one never travels through memory.
+// Row r of this problem is column r of the next factor's contraction, an item starts at a multiple of eight
+// row tiles, so its rows are whole 128-column blocks of that contraction: the item's results go to LDS, the
+// next factor's envelope rows of the item arrive in one more ring stage, and wave w builds the record of the
+// item's w-th block from the two with the arithmetic of the scale-in kernel (the same products, exponents and
+// limbs: bit-identical records).
+template <bool BATCH, int RANK, int R, bool FUSE>
 __global__ __launch_bounds__(kThreads)
-void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single) {
+void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb single,
+                     const StageProb* __restrict__ next_probs) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -615,15 +650,16 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
   // both roles walk the same stage sequence (see loader_role); one barrier per stage
   if (wave >= kComputeWaves) {
     static_assert(kLoaderWaves == 2, "one instantiation of the loader role per loader wave");
-    if (wave == kComputeWaves) loader_role<BATCH, RANK, 0, R>(items, single, item0, i_hi, stride, smem, lane);
-    else loader_role<BATCH, RANK, 1, R>(items, single, item0, i_hi, stride, smem, lane);
+    if (wave == kComputeWaves) loader_role<BATCH, RANK, 0, R, FUSE>(items, single, item0, i_hi, stride, smem, lane, next_probs);
+    else loader_role<BATCH, RANK, 1, R, FUSE>(items, single, item0, i_hi, stride, smem, lane, next_probs);
     return;
   }
 
   // =========================== contraction waves ===========================
   const SignConsts sconst = sign_consts();
+  float* zbuf = reinterpret_cast<float*>(smem + Geo<R>::kSmemBytes);   // (fused launches)
   int item = item0;
-  ItemInfo it = load_item<BATCH, R>(items, single, item);
+  ItemInfo it = load_item<BATCH, R, FUSE>(items, single, item, next_probs);
   int slot = 0;
   for (;;) {
     const int nr = max(0, min(R, it.ntl - wave * R));   // valid tiles of this wave (it owns tiles wave * R ..)
@@ -666,14 +702,49 @@ void stage_mx_kernel(const WorkItem* __restrict__ items, int nitems, StageProb s
             const int sel = n & 3;
             const float res = sel == 0 ? v[0] : sel == 1 ? v[1] : sel == 2 ? v[2] : v[3];
             const int row = (it.tile0 + trel) * kTileRows + 4 * kg + n;
-            if (n < 4 && row < it.rows) emit_result(it.out, (int64_t)b * it.out_ld + row, it.out_dt, res, it.flags);
+            if (FUSE) {
+              if (n < 4) zbuf[trel * kTileRows + 4 * kg + n] = (row < it.rows) ? res : 0.f;
+            } else {
+              if (n < 4 && row < it.rows) emit_result(it.out, (int64_t)b * it.out_ld + row, it.out_dt, res, it.flags);
+            }
+          } else if (FUSE) {
+            if (n < 4) zbuf[(wave * R + r) * kTileRows + 4 * kg + n] = 0.f;   // rows past the item's end
           }
+        }
+      }
+      if (FUSE) {
+        // ---- the next factor's records of this item's blocks (the barrier also publishes zbuf)
+        __syncthreads();
+        const _Float16* qh = reinterpret_cast<const _Float16*>(smem + slot * Geo<R>::kStageBytes);
+        slot = (slot + 1 == kStages) ? 0 : slot + 1;
+        const int nblk = (it.ntl * kTileRows + kBlockCols - 1) / kBlockCols;
+        if (wave < nblk) {
+          const int q2 = (it.tile0 * kTileRows) / kBlockCols + wave;
+          const int nsrc = n & (RANK - 1);
+          float val[32];
+          float m = 0.f;
+#pragma unroll
+          for (int j = 0; j < 32; ++j) {
+            const float presc = (j < 8) ? 2.f : (j < 16 ? 1.f : (j < 24 ? 0.5f : -0.5f));
+            const int rowi = wave * kBlockCols + local_col_of_element(j, 0) + 8 * kg;   // row inside the item
+            float prod;
+            {
+              // rounded to fp32 by itself, as the scale-in kernel leaves it in LDS (not fused into the
+              // subtraction of the first limb that follows): the same records bit for bit
+#pragma clang fp contract(off)
+              prod = (float)qh[rowi * RANK + nsrc] * zbuf[rowi];
+            }
+            val[j] = prod * presc;
+            m = fmaxf(m, fabsf(val[j]));
+          }
+          quantise_store<RANK == 8, false>(val, m, lane,
+                                           it.xs_next + ((size_t)b * it.KB_next + q2) * (size_t)kBlockBytes);
         }
       }
     }
     item += stride;
     if (item >= i_hi) break;
-    it = load_item<BATCH, R>(items, single, item);
+    it = load_item<BATCH, R, FUSE>(items, single, item, next_probs);
   }
 }
 
@@ -837,36 +908,50 @@ __global__ __launch_bounds__(64 * kSplitWaves) void stage_mx_split_kernel(SplitA
 
 static int max_workgroups() { return kWgsPerCu * compute_units(); }
 
-template <bool BATCH, int RANK, int R>
-static int launch_brr(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
+template <bool BATCH, int RANK, int R, bool FUSE>
+static int launch_brrf(const WorkItem* items_dev, int nitems, const StageProb* single, const StageProb* next_probs,
+                       hipStream_t s) {
+  constexpr int kSmem = Geo<R>::kSmemBytes + (FUSE ? Geo<R>::kZBytes : 0);
+  static_assert(kSmem <= 160 * 1024, "ring and result buffer fit the LDS of a compute unit");
   static KernelSetup setup;
   if (int e = kernel_setup(setup, [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH, RANK, R>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, Geo<R>::kSmemBytes);
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&stage_mx_kernel<BATCH, RANK, R, FUSE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
       }))
     return e;
   const int max_wgs = max_workgroups();
   const int nwg = nitems < max_wgs ? nitems : max_wgs;
-  hipLaunchKernelGGL((stage_mx_kernel<BATCH, RANK, R>), dim3((unsigned)nwg), dim3(kThreads), Geo<R>::kSmemBytes, s,
-                     items_dev, nitems, *single);
+  hipLaunchKernelGGL((stage_mx_kernel<BATCH, RANK, R, FUSE>), dim3((unsigned)nwg), dim3(kThreads), kSmem, s, items_dev,
+                     nitems, *single, next_probs);
   return (int)hipGetLastError();
+}
+
+template <bool BATCH, int RANK, int R>
+static int launch_brr(const WorkItem* items_dev, int nitems, const StageProb* single, const StageProb* next_probs,
+                      hipStream_t s) {
+  if constexpr (BATCH) {
+    if (next_probs) return launch_brrf<BATCH, RANK, R, true>(items_dev, nitems, single, next_probs, s);
+  }
+  return launch_brrf<BATCH, RANK, R, false>(items_dev, nitems, single, nullptr, s);
 }
 
 // item_tiles: row tiles per work item of the launch, 8 R
 template <bool BATCH, int RANK>
-static int launch_br(const WorkItem* items_dev, int nitems, int item_tiles, const StageProb* single, hipStream_t s) {
+static int launch_br(const WorkItem* items_dev, int nitems, int item_tiles, const StageProb* single,
+                     const StageProb* next_probs, hipStream_t s) {
   switch (item_tiles) {
-    case 64: return launch_brr<BATCH, RANK, 8>(items_dev, nitems, single, s);
-    case 56: return launch_brr<BATCH, RANK, 7>(items_dev, nitems, single, s);
-    case 48: return launch_brr<BATCH, RANK, 6>(items_dev, nitems, single, s);
+    case 64: return launch_brr<BATCH, RANK, 8>(items_dev, nitems, single, next_probs, s);
+    case 56: return launch_brr<BATCH, RANK, 7>(items_dev, nitems, single, next_probs, s);
+    case 48: return launch_brr<BATCH, RANK, 6>(items_dev, nitems, single, next_probs, s);
     default: return (int)hipErrorInvalidValue;
   }
 }
 
 template <bool BATCH>
-static int launch_b(const WorkItem* items_dev, int nitems, int item_tiles, const StageProb* single, hipStream_t s) {
-  if (single->l == 8) return launch_br<BATCH, 8>(items_dev, nitems, item_tiles, single, s);
-  return launch_br<BATCH, 16>(items_dev, nitems, item_tiles, single, s);
+static int launch_b(const WorkItem* items_dev, int nitems, int item_tiles, const StageProb* single,
+                    const StageProb* next_probs, hipStream_t s) {
+  if (single->l == 8) return launch_br<BATCH, 8>(items_dev, nitems, item_tiles, single, next_probs, s);
+  return launch_br<BATCH, 16>(items_dev, nitems, item_tiles, single, next_probs, s);
 }
 
 }  // namespace mx
@@ -919,14 +1004,15 @@ bool stage_is_mx(const StageProb& p) {
          packed_words(p.rows, p.K) * 4u < (1ull << 31);
 }
 
-int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, hipStream_t s) {
+int launch_stage_mx(const WorkItem* items_dev, int nitems, const StageProb* single, const StageProb* next_probs_dev,
+                    hipStream_t s) {
   if (!items_dev) {
     const int item_tiles = mx_pick_item_tiles(1, &single->ntiles, &single->KB);
     nitems = (single->ntiles + item_tiles - 1) / item_tiles;
-    return mx::launch_b<false>(nullptr, nitems, item_tiles, single, s);
+    return mx::launch_b<false>(nullptr, nitems, item_tiles, single, nullptr, s);
   }
   // single->ntiles carries the plan's tiles per item of this stage
-  return mx::launch_b<true>(items_dev, nitems, single->ntiles, single, s);
+  return mx::launch_b<true>(items_dev, nitems, single->ntiles, single, next_probs_dev, s);
 }
 
 SplitGeom split_geom(int ntiles, int KB) {

@@ -312,6 +312,29 @@ def test_block_scaled_plan_cuts_the_last_partial_round_into_pieces():
     _covered_once(tables[0], shapes, 0)
 
 
+def test_launches_per_plan():
+    """Both factors on the block-scaled kernel: three launches (scale-in, product + the next factor's records,
+    product); a small plan on the fp16-staged kernels: four; many tokens: two."""
+    L = mb.lib()
+    def launches(shapes, T=1):
+        n = len(shapes)
+        arr = (mb.Layer * n)()
+        for i, (m, nn, k) in enumerate(shapes):
+            arr[i].desc = mb.Desc(m, nn, k, 16, 0, 0, 0, 0)
+            arr[i].SA_packed_dev = arr[i].SB_packed_dev = arr[i].X_dev = arr[i].Y_dev = FAKE
+            arr[i].env = mb.Env(FAKE, FAKE, FAKE, FAKE)
+            arr[i].ldx, arr[i].ldy, arr[i].T = nn, m, T
+        pb, wb = C.c_size_t(0), C.c_size_t(0)
+        assert L.mdbf_batch_plan_bytes(n, arr, C.byref(pb), C.byref(wb)) == 0
+        buf = C.create_string_buffer(pb.value)
+        assert L.mdbf_batch_plan_build(n, arr, FAKE, wb.value, buf, pb.value) == 0
+        return L.mdbf_batch_plan_launches(buf, pb.value)
+    assert launches([(4096, 4096, 2656)] * 336) == 3
+    assert launches([(4096, 4096, 2656)] * 3) == 4
+    assert launches([(4096, 4096, 2656)] * 8, T=8) == 2
+    assert L.mdbf_batch_plan_launches(None, 0) == -1
+
+
 def test_block_scaled_plan_picks_the_item_size_that_wastes_fewest_tile_slots():
     """166 row tiles are three items of 56 tiles (56 + 56 + 54), not 64 + 64 + 38: the same number of items, an
     eighth fewer sign words moved per item and no idle waves in the third.  256 row tiles stay four items of
