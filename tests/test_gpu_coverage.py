@@ -300,3 +300,25 @@ def test_plan_whose_last_round_is_cut_into_pieces(gpu):
     torch.cuda.synchronize()
     for Yb, ref in zip(Ys, refs):
         assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
+
+
+def test_plan_whose_first_factor_is_cut_into_pieces_and_writes_the_next_records(gpu):
+    """320 equal layers with 64 row tiles in the first factor: 320 work items = 1.25 rounds of 256 workgroups, so the
+    last round's items are cut into 16-tile pieces, each of which writes the two 128-column blocks of the second
+    factor's activation records that its rows make up (three launches per run).  Every output against the oracle."""
+    torch, mb = gpu
+    layers, Xs, Ys, refs = [], [], [], []
+    for i in range(320):
+        L = synth.make_layer(256, 384, 1024, 16, seed=9500 + i, env_dtype="f16", env_kind="llama", signed_env=True)
+        X = synth.make_activations(384, 1, seed=9900 + i, x_dtype="f16")
+        layers.append(mb.DeviceLayer.from_host(L))
+        Xs.append(_to_dev(torch, X))
+        Ys.append(torch.zeros((1, 256), dtype=torch.float32, device="cuda:0"))
+        refs.append(orc.forward_factored(*_oracle_args(L), X))
+    plan = mb.BatchPlan(layers, Xs, Ys, block_scaled=True)
+    assert plan.kernel(1) == "stage_mx_kernel" and plan.kernel(2) == "stage_mx_kernel" and plan.launches() == 3
+    for _ in range(2):
+        plan.run()
+    torch.cuda.synchronize()
+    for Yb, ref in zip(Ys, refs):
+        assert orc.max_rel_error(Yb.cpu().numpy(), ref) <= TOL
