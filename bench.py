@@ -280,6 +280,30 @@ def main():
         torch.cuda.synchronize()
         us_call = e0.elapsed_time(e1) * 1e3 / (reps * a.copies)
         extras["per_call_graph"] = {"us_per_call": us_call, "GB/s": bytes_call / us_call / 1e3}
+        # (1b) the same calls captured on four streams: the layers are independent, so the graph may have
+        #      parallel branches and the device runs several calls' launches side by side
+        side = [torch.cuda.Stream() for _ in range(3)]
+        g4 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g4, stream=s):
+            for st in side:
+                st.wait_stream(s)
+            branches = [s] + side
+            for i in range(a.copies):
+                mb.mdbf_forward(layers[i], Xs[i], y_dtype="f16", Y=Ys[i], workspace=ws[i], stream=branches[i % 4])
+            for st in side:
+                s.wait_stream(st)
+        g4.replay()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            g4.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us4 = e0.elapsed_time(e1) * 1e3 / (reps * a.copies)
+        err4, _ = oracle_check(torch, mb, layers[2], Xs[2], Ys[2])
+        extras["per_call_graph_4_branches"] = {"us_per_call": us4, "GB/s": bytes_call / us4 / 1e3,
+                                               "max_rel_err_vs_oracle": err4}
+        del g4
         # (2) the same layer again and again (cache resident) through the batched entry point
         hot = mb.BatchPlan([layers[0]] * 64, [Xs[0]] * 64, [Ys[0]] * 64)
         preheat(torch, hot.run, a.preheat_ms)
